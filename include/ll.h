@@ -1,0 +1,131 @@
+/*
+ * ll.h - C ABI of the fused logit-lens projection and steering library (MI355X, gfx950).
+ *
+ * All tensor pointers are DEVICE pointers owned by the caller; they must stay
+ * valid until the stream has finished the call's work.  No entry point
+ * allocates or frees device memory, and none synchronises the stream unless
+ * its comment says so.  `stream` is a hipStream_t passed as void* (NULL = the
+ * default stream).  bf16 tensors are raw 16-bit patterns, row-major.
+ *
+ * Return value: 0 on success, a negative LL_E* code otherwise.  On error no
+ * output is defined; nothing is thrown and the process is never aborted.
+ */
+#ifndef LL_H_
+#define LL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LL_OK           0
+#define LL_EINVAL      -1   /* null required pointer, bad size, k out of range, d not a multiple of 8 */
+#define LL_EWORKSPACE  -2   /* workspace missing or smaller than ll_workspace_bytes()              */
+#define LL_EHIP        -3   /* a HIP call failed; ll_last_hip_error() gives its code                */
+
+#define LL_KMAX         32  /* largest supported top-k */
+
+/* N lens rows (layer x token pairs, row r = l*T + t of the packed trajectories,
+ * paper Sec. 3.1 Stage 3), hidden size d, vocabulary size V. */
+typedef struct ll_shape {
+  int64_t N;
+  int32_t d;
+  int32_t V;
+} ll_shape;
+
+/* Bytes of device workspace ll_project needs for this shape and k.  Pure host
+ * arithmetic (no HIP call).  Returns 0 for an invalid shape or k. */
+size_t ll_workspace_bytes(const ll_shape* shape, int k);
+
+/*
+ * Deferred, batched logit-lens projection (paper Sec. 3.3, Eq. 1 and "Top-k
+ * extraction"; Alg. 1, Phase 2), fused so that the [N, V] logits never reach
+ * memory:
+ *
+ *   a[r, :]  = bf16( gamma * hidden[r, :] / sqrt(mean_j hidden[r, j]^2 + eps) )   (final RMSNorm)
+ *   z[r, v]  = sum_j a[r, j] * W_U[v, j]                                            (Eq. 1, b = 0)
+ *   p[r, :]  = softmax over the whole vocabulary
+ *
+ * Outputs, per row r:
+ *   out_topk_ids [N, k] int32  ids of the k largest logits, descending logit, ascending id on exact ties
+ *   out_topk_p   [N, k] fp32   their full-softmax probabilities
+ *   out_target_logp [N] fp32   z[r, target_ids[r]] - logsumexp(z[r, :]); NaN if the id is outside [0, V)
+ *   out_entropy  [N] fp32      -sum_v p log p, in nats
+ *
+ *   hidden      bf16 [N, d]
+ *   gamma       bf16 [d], or NULL: the rows are already normalised (e.g. the output of
+ *               ll_steer_inject) and are used as they are
+ *   W_U         bf16 [V, d]
+ *   target_ids  int32 [N], or NULL: out_target_logp is not written (and may be NULL)
+ *   workspace   device scratch of at least ll_workspace_bytes(shape, k) bytes, 256-byte aligned
+ *
+ * Requirements: d a positive multiple of 8, 1 <= k <= min(LL_KMAX, V), all tensors 16-byte
+ * aligned.  N == 0 is a successful no-op.  Rows are processed in passes of at most 8192 rows
+ * so the workspace does not grow with N beyond 4 bytes per row.
+ * Arithmetic: bf16 operands, fp32 accumulation and fp32 softmax statistics.
+ * Everything is enqueued on `stream`; the call returns without waiting.
+ */
+int ll_project(const ll_shape* shape, void* workspace, size_t workspace_bytes,
+               const void* hidden, const void* gamma, const void* W_U,
+               float eps, int k, const int32_t* target_ids,
+               int32_t* out_topk_ids, float* out_topk_p,
+               float* out_target_logp, float* out_entropy,
+               void* stream);
+
+/*
+ * ll_project with per-phase timing, for benchmarks.  Same arguments and results; in addition
+ * phase_ms (HOST pointer, 3 floats) receives the GPU time in milliseconds, summed over the row
+ * passes, of {RMS statistics, fused projection kernel, split merge}, measured with HIP events
+ * on `stream`.  Unlike ll_project this call creates events and SYNCHRONISES the stream before
+ * it returns.
+ */
+int ll_project_timed(const ll_shape* shape, void* workspace, size_t workspace_bytes,
+                     const void* hidden, const void* gamma, const void* W_U,
+                     float eps, int k, const int32_t* target_ids,
+                     int32_t* out_topk_ids, float* out_topk_p,
+                     float* out_target_logp, float* out_entropy,
+                     void* stream, float* phase_ms);
+
+/*
+ * Steering direction (paper Sec. 3.4, Eq. 2): v = (y+ - y-) / ||y+ - y-||_2 with y+ the mean
+ * of the n_target rows of `target` and y- the mean of the n_base rows of `base` (hidden states
+ * taken at the label-token position, Sec. 4 steering protocol).  The rows are used as given.
+ *
+ *   base, target  bf16 [n_base, d], [n_target, d]; n_base, n_target >= 1
+ *   normalize     1: Eq. 2; 0: the raw difference of means.  A zero difference gives v = 0.
+ *   out_v         fp32 [d]
+ *   workspace     optional device scratch (may be NULL): with at least
+ *                 ll_steer_workspace_bytes(d) bytes the row reduction is spread over the whole
+ *                 GPU; without it a narrower launch is used.  Results are deterministic either
+ *                 way (no atomics), but the two paths may differ in the last fp32 bit.
+ */
+size_t ll_steer_workspace_bytes(int32_t d);
+int ll_steer_vector(const void* base, int64_t n_base, const void* target, int64_t n_target,
+                    int32_t d, int normalize, float* out_v,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Steering injection after the final norm (paper Sec. 3.4, Eq. 3, applied post-normalisation):
+ *
+ *   out[r, j] = bf16( gamma[j] * hidden[r, j] / sqrt(mean_j hidden[r, j]^2 + eps) + alpha * v[j] )
+ *
+ *   shape       N and d are used, V is ignored
+ *   hidden      bf16 [N, d];  gamma bf16 [d] (required);  v fp32 [d]
+ *   out_hidden  bf16 [N, d]; may be the same buffer as `hidden` (in place), no other overlap
+ * The result is what ll_project expects with gamma == NULL.  alpha == 0 gives bf16(RMSNorm(h)).
+ */
+int ll_steer_inject(const ll_shape* shape, const void* hidden, const void* gamma, float eps,
+                    const float* v, float alpha, void* out_hidden, void* stream);
+
+/* Text for an LL_E* code (static storage, never NULL). */
+const char* ll_error_string(int code);
+
+/* The hipError_t value of the last failed HIP call in this thread (0 if none). */
+int ll_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LL_H_ */

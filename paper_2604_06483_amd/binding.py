@@ -1,0 +1,162 @@
+"""ctypes binding of the C-ABI library (include/ll.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of libll.so.
+PyTorch supplies device memory and the stream.  If the library has not been built
+(`python -m paper_2604_06483_amd.build`) loading raises: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
+
+import torch
+
+LL_OK, LL_EINVAL, LL_EWORKSPACE, LL_EHIP = 0, -1, -2, -3
+LL_KMAX = 32
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libll.so")
+_lib = None
+
+
+class ll_shape(Structure):
+    _fields_ = [("N", c_int64), ("d", c_int32), ("V", c_int32)]
+
+
+class LLError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().ll_error_string(code).decode()
+        if code == LL_EHIP:
+            msg += f" [hipError {lib().ll_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} ({code})")
+
+
+_PROJECT_ARGS = [POINTER(ll_shape), c_void_p, c_size_t, c_void_p, c_void_p, c_void_p, c_float, c_int,
+                 c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library with its prototypes set."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2604_06483_amd.build`")
+        L = ctypes.CDLL(_LIB_PATH)
+        L.ll_workspace_bytes.argtypes = [POINTER(ll_shape), c_int]
+        L.ll_workspace_bytes.restype = c_size_t
+        L.ll_project.argtypes = _PROJECT_ARGS
+        L.ll_project.restype = c_int
+        L.ll_project_timed.argtypes = _PROJECT_ARGS + [POINTER(c_float)]
+        L.ll_project_timed.restype = c_int
+        L.ll_steer_workspace_bytes.argtypes = [c_int32]
+        L.ll_steer_workspace_bytes.restype = c_size_t
+        L.ll_steer_vector.argtypes = [c_void_p, c_int64, c_void_p, c_int64, c_int32, c_int, c_void_p,
+                                      c_void_p, c_size_t, c_void_p]
+        L.ll_steer_vector.restype = c_int
+        L.ll_steer_inject.argtypes = [POINTER(ll_shape), c_void_p, c_void_p, c_float, c_void_p, c_float,
+                                      c_void_p, c_void_p]
+        L.ll_steer_inject.restype = c_int
+        L.ll_error_string.argtypes = [c_int]
+        L.ll_error_string.restype = c_char_p
+        L.ll_last_hip_error.argtypes = []
+        L.ll_last_hip_error.restype = c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _check(t, dtype, name, shape=None):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: need a contiguous {dtype} tensor on the GPU")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return c_void_p(s.cuda_stream)
+
+
+def ll_workspace_bytes(N: int, d: int, V: int, k: int) -> int:
+    return int(lib().ll_workspace_bytes(ll_shape(N, d, V), k))
+
+
+def ll_steer_workspace_bytes(d: int) -> int:
+    return int(lib().ll_steer_workspace_bytes(d))
+
+
+def ll_project(hidden, gamma, W_U, eps, k, target_ids=None, *, workspace=None, stream=None, out=None, timed=False):
+    """hidden [..., d] bf16, gamma [d] bf16 or None, W_U [V, d] bf16, target_ids [N] int32 or None.
+
+    Returns (topk_ids [N,k] int32, topk_p [N,k] fp32, target_logp [N] fp32 or None, entropy [N] fp32),
+    plus the three phase times in ms when timed=True (that variant synchronises the stream).
+    """
+    d = hidden.shape[-1]
+    h2 = hidden.reshape(-1, d)
+    N = h2.shape[0]
+    V = W_U.shape[0]
+    _check(h2, torch.bfloat16, "hidden")
+    _check(W_U, torch.bfloat16, "W_U", (V, d))
+    if gamma is not None:
+        _check(gamma, torch.bfloat16, "gamma", (d,))
+    if target_ids is not None:
+        _check(target_ids, torch.int32, "target_ids", (N,))
+    shape = ll_shape(N, d, V)
+    need = int(lib().ll_workspace_bytes(shape, k))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=hidden.device)
+    dev = hidden.device
+    if out is None:
+        ids = torch.empty((N, k), dtype=torch.int32, device=dev)
+        p = torch.empty((N, k), dtype=torch.float32, device=dev)
+        logp = torch.empty((N,), dtype=torch.float32, device=dev) if target_ids is not None else None
+        ent = torch.empty((N,), dtype=torch.float32, device=dev)
+    else:
+        ids, p, logp, ent = out
+    args = [shape, _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(h2), _ptr(gamma), _ptr(W_U),
+            float(eps), int(k), _ptr(target_ids), _ptr(ids), _ptr(p), _ptr(logp), _ptr(ent), _stream(stream)]
+    if timed:
+        ms = (c_float * 3)()
+        rc = lib().ll_project_timed(*args, ms)
+        if rc != LL_OK:
+            raise LLError(rc, "ll_project_timed")
+        return ids, p, logp, ent, [float(x) for x in ms]
+    rc = lib().ll_project(*args)
+    if rc != LL_OK:
+        raise LLError(rc, "ll_project")
+    return ids, p, logp, ent
+
+
+def ll_steer_vector(base, target, normalize=True, *, workspace=None, stream=None, out=None):
+    """base [Nb, d], target [Nt, d] bf16 -> v [d] fp32 (paper Eq. 2)."""
+    _check(base, torch.bfloat16, "base")
+    _check(target, torch.bfloat16, "target")
+    d = base.shape[-1]
+    if target.shape[-1] != d or base.dim() != 2 or target.dim() != 2:
+        raise ValueError("base and target must be [rows, d] with the same d")
+    v = torch.empty((d,), dtype=torch.float32, device=base.device) if out is None else out
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().ll_steer_vector(_ptr(base), base.shape[0], _ptr(target), target.shape[0], d, int(bool(normalize)),
+                               _ptr(v), _ptr(workspace), wsb, _stream(stream))
+    if rc != LL_OK:
+        raise LLError(rc, "ll_steer_vector")
+    return v
+
+
+def ll_steer_inject(hidden, gamma, eps, v, alpha, *, stream=None, out=None):
+    """bf16(RMSNorm(hidden) + alpha v), same shape as hidden (paper Eq. 3, post-norm)."""
+    d = hidden.shape[-1]
+    h2 = hidden.reshape(-1, d)
+    _check(h2, torch.bfloat16, "hidden")
+    _check(gamma, torch.bfloat16, "gamma", (d,))
+    _check(v, torch.float32, "v", (d,))
+    o = torch.empty_like(h2) if out is None else out.reshape(-1, d)
+    rc = lib().ll_steer_inject(ll_shape(h2.shape[0], d, 0), _ptr(h2), _ptr(gamma), float(eps), _ptr(v), float(alpha),
+                               _ptr(o), _stream(stream))
+    if rc != LL_OK:
+        raise LLError(rc, "ll_steer_inject")
+    return o.reshape(hidden.shape)

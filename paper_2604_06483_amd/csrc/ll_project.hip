@@ -1,0 +1,533 @@
+// Fused logit-lens projection for gfx950: RMS statistics, bf16 MFMA GEMM over the vocabulary with
+// an online-softmax / top-k / target-gather epilogue, and the merge of the vocabulary splits.
+//
+// Follows the paper's Sec. 3.3 (Eq. 1 and "Top-k extraction") and Alg. 1 Phase 2; the logits of
+// Eq. 1 live only in MFMA accumulators.
+#include "ll_common.h"
+
+#include <limits.h>
+#include <math.h>
+
+#include <type_traits>
+
+namespace {
+
+using namespace ll;
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int BM = 256;          // vocabulary rows per tile (MFMA M side)
+constexpr int BN = 256;          // lens rows per workgroup (MFMA N side)
+constexpr int BK = 64;           // K step staged in LDS
+constexpr int NTHREADS = 256;    // 4 wavefronts, one per SIMD
+constexpr int CHUNK_ROWS = 8192; // lens rows per pass
+constexpr int MAX_SPLITS = 16;   // vocabulary splits per row block
+constexpr int QCAP = 8;          // top-k candidate queue entries per lane
+constexpr int NUM_XCD = 8;
+constexpr int NUM_CU = 256;
+constexpr float NEG_BIG = -3.0e38f;   // stands for "no logit" without the NaNs that -inf would breed
+constexpr float LOG2E = 1.4426950408889634f;
+
+// ---------------------------------------------------------------------------------------
+// a2: inv_rms[r] = 1 / sqrt(mean_j h[r,j]^2 + eps).  One wavefront per row, 16-byte loads.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void ll_rms_stats_kernel(const uint16_t* __restrict__ hidden, int64_t n_rows,
+                                                           int d, float eps, float* __restrict__ inv_rms) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n_rows) return;
+  const uint4* src = reinterpret_cast<const uint4*>(hidden + row * (int64_t)d);
+  const int n16 = d >> 3;
+  float acc0 = 0.f, acc1 = 0.f;
+  for (int c = lane; c < n16; c += 64) {
+    accum_sq(src[c], acc0, acc1);
+  }
+  const float ss = wave_sum(acc0 + acc1);
+  if (lane == 0) inv_rms[row] = inv_rms_from_sumsq(ss, d, eps);
+}
+
+// ---------------------------------------------------------------------------------------
+// a3..a7: the fused kernel.
+//
+// One workgroup owns BN = 256 lens rows and one vocabulary split; it sweeps the split's 256-wide
+// vocabulary tiles.  Per tile the logits Z^T[vocab, row] = W_tile . A^T are accumulated with
+// v_mfma_f32_32x32x16_bf16 (vocabulary on the M side, lens rows on the N side): wavefront w owns
+// lens rows [64w, 64w+64) against all 256 vocabulary rows, i.e. 8 x 2 accumulator tiles of
+// 32 x 32.  In that accumulator layout a lane holds 16 vocabulary entries of ONE lens row per
+// tile; after exchanging the two row tiles between the lane halves (v_permlane32_swap) lane l of
+// wavefront w holds all 256 logits of lens row 64w + l, so the whole epilogue is lane-private.
+// ---------------------------------------------------------------------------------------
+struct GemmArgs {
+  const uint16_t* A;        // [rows, d] bf16 (this pass's rows)
+  const float* inv_rms;     // [rows] or nullptr (rows already normalised)
+  const uint16_t* gamma;    // [d] or nullptr
+  const uint16_t* W;        // [V, d] bf16
+  const int32_t* target;    // [rows] or nullptr
+  float* stats;             // [rows, splits, 4]  (m, S, U, z_target)
+  float* topv;              // [rows, splits, k]
+  int32_t* topi;            // [rows, splits, k]
+  int rows, d, V, k, splits, tiles, row_blocks;
+};
+
+// LDS tile: [256 rows][8 chunks of 16 B]; chunk index XOR-swizzled with (row/2)%8 so that both the
+// 16-byte row-major stores and the MFMA fragment reads (32 consecutive rows, one chunk) spread
+// over all banks.
+__device__ __forceinline__ int lds_off(int row, int chunk) { return (row * 8 + (chunk ^ ((row >> 1) & 7))) * 16; }
+
+template <bool FUSED_NORM>
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void ll_lens_gemm_kernel(const GemmArgs p) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* sW = smem;
+  unsigned char* sA = smem + BM * BK * 2;
+  float* listV = reinterpret_cast<float*>(smem + (BM + BN) * BK * 2);
+  int* listI = reinterpret_cast<int*>(listV + p.k * BN);
+  float* queV = reinterpret_cast<float*>(listI + p.k * BN);
+  int* queI = reinterpret_cast<int*>(queV + QCAP * NTHREADS);
+
+  // Workgroup ids are dealt round-robin over the 8 XCDs; remap so that one XCD (one L2) gets a
+  // compact rectangle of (row blocks) x (all splits) and its CUs share A panels and W tiles.
+  const int per_xcd = gridDim.x / NUM_XCD;
+  const int logical = (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+  if (logical >= p.row_blocks * p.splits) return;
+  const int split = logical % p.splits;
+  const int rb = logical / p.splits;
+  const int tile0 = (int)((int64_t)split * p.tiles / p.splits);
+  const int tile1 = (int)((int64_t)(split + 1) * p.tiles / p.splits);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int d = p.d, V = p.V, k = p.k;
+
+  // --- global -> LDS staging map: thread handles physical chunk (tid % 8) of rows tid/8 + 32 i.
+  const int ld_row = tid >> 3;
+  const int ld_chunk = (tid & 7) ^ ((ld_row >> 1) & 7);     // logical K chunk this thread fetches
+  const int st_off = (ld_row * 8 + (tid & 7)) * 16;          // + i * 32 rows * 128 B
+
+  const uint16_t* a_ptr[8];
+  float a_scale[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    int r = rb * BN + ld_row + 32 * i;
+    r = r < p.rows ? r : p.rows - 1;
+    a_ptr[i] = p.A + (int64_t)r * d + ld_chunk * 8;
+    a_scale[i] = FUSED_NORM ? p.inv_rms[r] : 1.0f;
+  }
+
+  // --- MFMA fragment map: lane reads row (lane % 32) of each 32-row group, K chunk 2*kk + lane/32.
+  const int f_row = lane & 31;
+  const int f_half = lane >> 5;
+
+  // --- epilogue state: this lane owns lens row (rb*BN + tid).
+  const int my_row = rb * BN + tid;
+  float m_run = -INFINITY, s_run = 0.f, u_run = 0.f, z_tgt = -INFINITY;
+  float tau = -INFINITY;
+  int tau_id = INT_MAX;
+  const int tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
+  for (int j = 0; j < k; ++j) {
+    listV[j * BN + tid] = -INFINITY;
+    listI[j * BN + tid] = INT_MAX;
+  }
+
+  const int KT = (d + BK - 1) / BK;
+
+  for (int tile = tile0; tile < tile1; ++tile) {
+    const int v0 = tile * BM;
+    const uint16_t* w_ptr[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int v = v0 + ld_row + 32 * i;
+      v = v < V ? v : V - 1;
+      w_ptr[i] = p.W + (int64_t)v * d + ld_chunk * 8;
+    }
+
+    f32x16 acc[8][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    uint4 wreg[8], areg[8], greg;
+    auto fetch = [&](int kt) {
+      const int koff = kt * BK;
+      const bool in = koff + ld_chunk * 8 < d;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        wreg[i] = in ? *reinterpret_cast<const uint4*>(w_ptr[i] + koff) : make_uint4(0, 0, 0, 0);
+        areg[i] = in ? *reinterpret_cast<const uint4*>(a_ptr[i] + koff) : make_uint4(0, 0, 0, 0);
+      }
+      if (FUSED_NORM) greg = in ? *reinterpret_cast<const uint4*>(p.gamma + koff + ld_chunk * 8) : make_uint4(0, 0, 0, 0);
+    };
+
+    fetch(0);
+    for (int kt = 0; kt < KT; ++kt) {
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        *reinterpret_cast<uint4*>(sW + st_off + i * 32 * 128) = wreg[i];
+        uint4 a = areg[i];
+        if (FUSED_NORM) {
+          // a3: a = bf16((h * inv_rms) * gamma), one rounding
+          const float s = a_scale[i];
+          const uint32_t gw[4] = {greg.x, greg.y, greg.z, greg.w};
+          uint32_t aw[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            aw[q] = pack_bf16(bf16_lo(aw[q]) * s * bf16_lo(gw[q]), bf16_hi(aw[q]) * s * bf16_hi(gw[q]));
+          a = make_uint4(aw[0], aw[1], aw[2], aw[3]);
+        }
+        *reinterpret_cast<uint4*>(sA + st_off + i * 32 * 128) = a;
+      }
+      __syncthreads();
+      if (kt + 1 < KT) fetch(kt + 1);
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        const int chunk = 2 * kk + f_half;
+        bf16x8 fa[2], fw[8];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          fa[j] = *reinterpret_cast<const bf16x8*>(sA + lds_off(wave * 64 + j * 32 + f_row, chunk));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(sW + lds_off(i * 32 + f_row, chunk));
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+      }
+    }
+
+    // ------------------------------ epilogue ------------------------------
+    const bool partial = v0 + BM > V;
+    const int tl = tgt - v0;       // target position inside this tile, if in [0, 256)
+    auto group = [&](auto group_index) {
+      constexpr int i = decltype(group_index)::value;
+      // x[o]: logit of vocabulary entry v0 + 32 i + o for this lane's row.
+      float x[32];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][0][r]), __float_as_uint(acc[i][1][r]),
+                                                   false, false);
+        const int o = 8 * (r >> 2) + (r & 3);
+        x[o] = __uint_as_float(sw[0]);
+        x[o + 4] = __uint_as_float(sw[1]);
+      }
+      const int g0 = v0 + 32 * i;
+      if (partial) {
+#pragma unroll
+        for (int o = 0; o < 32; ++o)
+          if (g0 + o >= V) x[o] = NEG_BIG;
+      }
+      // a7: target gather
+      if (__builtin_amdgcn_ballot_w64((unsigned)(tl - 32 * i) < 32u) != 0) {
+#pragma unroll
+        for (int o = 0; o < 32; ++o)
+          if (tl == 32 * i + o) z_tgt = x[o];
+      }
+      // a5: online max / sum-exp / sum exp*(z-m)
+      float gmax = x[0];
+#pragma unroll
+      for (int o = 1; o < 32; ++o) gmax = fmaxf(gmax, x[o]);
+      const float m_new = fmaxf(m_run, gmax);
+      if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+        const float dm = (m_run == -INFINITY) ? 0.f : m_run - m_new;
+        const float sc = __builtin_amdgcn_exp2f(dm * LOG2E);
+        u_run = sc * fmaf(dm, s_run, u_run);
+        s_run = sc * s_run;
+        m_run = m_new;
+      }
+      const float mb = m_run * LOG2E;
+      float s4[4] = {0.f, 0.f, 0.f, 0.f}, u4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int o = 0; o < 32; ++o) {
+        const float e = __builtin_amdgcn_exp2f(fmaf(x[o], LOG2E, -mb));
+        s4[o & 3] += e;
+        u4[o & 3] = fmaf(e, x[o] - m_run, u4[o & 3]);
+      }
+      s_run += (s4[0] + s4[1]) + (s4[2] + s4[3]);
+      u_run += (u4[0] + u4[1]) + (u4[2] + u4[3]);
+
+      // a6: streaming top-k.  Values that reach the current k-th best go through a small
+      // per-lane queue in LDS and are then inserted into the lane's sorted list; the queue is
+      // filled in windows of QCAP hits so that any number of hits is handled.
+      const float tau_scan = tau;
+      for (unsigned base = 0;; base += QCAP) {
+        unsigned cnt = 0;
+#pragma unroll
+        for (int o = 0; o < 32; ++o) {
+          if (x[o] >= tau_scan) {
+            const unsigned pos = cnt - base;
+            if (pos < (unsigned)QCAP) {
+              queV[pos * NTHREADS + tid] = x[o];
+              queI[pos * NTHREADS + tid] = g0 + o;
+            }
+            ++cnt;
+          }
+        }
+        if (__builtin_amdgcn_ballot_w64(cnt > base) == 0) break;
+        const unsigned n = cnt > base ? (cnt - base < (unsigned)QCAP ? cnt - base : (unsigned)QCAP) : 0u;
+        for (unsigned q = 0; q < n; ++q) {
+          const float z = queV[q * NTHREADS + tid];
+          const int id = queI[q * NTHREADS + tid];
+          if (id < V && (z > tau || (z == tau && id < tau_id))) {
+            int j = k - 1;
+            while (j > 0) {
+              const float pv = listV[(j - 1) * BN + tid];
+              const int pi = listI[(j - 1) * BN + tid];
+              if (pv > z || (pv == z && pi < id)) break;
+              listV[j * BN + tid] = pv;
+              listI[j * BN + tid] = pi;
+              --j;
+            }
+            listV[j * BN + tid] = z;
+            listI[j * BN + tid] = id;
+            tau = listV[(k - 1) * BN + tid];
+            tau_id = listI[(k - 1) * BN + tid];
+          }
+        }
+        if (__builtin_amdgcn_ballot_w64(cnt > base + QCAP) == 0) break;
+      }
+    };
+    group(std::integral_constant<int, 0>{});
+    group(std::integral_constant<int, 1>{});
+    group(std::integral_constant<int, 2>{});
+    group(std::integral_constant<int, 3>{});
+    group(std::integral_constant<int, 4>{});
+    group(std::integral_constant<int, 5>{});
+    group(std::integral_constant<int, 6>{});
+    group(std::integral_constant<int, 7>{});
+  }
+
+  // ---- per-(row, split) partial results
+  if (my_row < p.rows) {
+    const int64_t o = (int64_t)my_row * p.splits + split;
+    reinterpret_cast<float4*>(p.stats)[o] = make_float4(m_run, s_run, u_run, z_tgt);
+    for (int j = 0; j < k; ++j) {
+      p.topv[o * k + j] = listV[j * BN + tid];
+      p.topi[o * k + j] = listI[j * BN + tid];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// a8: merge the splits of each row and finalise.  One thread per row.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void ll_merge_kernel(const float* __restrict__ stats, const float* __restrict__ topv,
+                                                       const int32_t* __restrict__ topi, int rows, int splits, int k, int V,
+                                                       const int32_t* __restrict__ target, int32_t* __restrict__ out_ids,
+                                                       float* __restrict__ out_p, float* __restrict__ out_logp,
+                                                       float* __restrict__ out_entropy) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= rows) return;
+  const float4* st = reinterpret_cast<const float4*>(stats) + (int64_t)row * splits;
+  float M = -INFINITY;
+  for (int s = 0; s < splits; ++s) M = fmaxf(M, st[s].x);
+  float S = 0.f, U = 0.f, zt = -INFINITY;
+  for (int s = 0; s < splits; ++s) {
+    const float4 q = st[s];
+    const float dm = q.x - M;
+    const float sc = __builtin_amdgcn_exp2f(dm * LOG2E);
+    S += sc * q.y;
+    U += sc * fmaf(dm, q.y, q.z);
+    zt = fmaxf(zt, q.w);
+  }
+  const float logS = logf(S);
+  out_entropy[row] = logS - U / S;
+  if (target != nullptr) {
+    const int t = target[row];
+    out_logp[row] = (t >= 0 && t < V) ? (zt - M) - logS : __builtin_nanf("");
+  }
+  // k-way merge of the per-split sorted lists (descending logit, ascending id).
+  int head[MAX_SPLITS];
+#pragma unroll
+  for (int s = 0; s < MAX_SPLITS; ++s) head[s] = 0;
+  const float* tv = topv + (int64_t)row * splits * k;
+  const int32_t* ti = topi + (int64_t)row * splits * k;
+  for (int j = 0; j < k; ++j) {
+    float bz = -INFINITY;
+    int bi = INT_MAX, bs = 0;
+#pragma unroll
+    for (int s = 0; s < MAX_SPLITS; ++s) {
+      if (s < splits && head[s] < k) {
+        const float z = tv[s * k + head[s]];
+        const int id = ti[s * k + head[s]];
+        if (z > bz || (z == bz && id < bi)) {
+          bz = z;
+          bi = id;
+          bs = s;
+        }
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < MAX_SPLITS; ++s)
+      if (s == bs) ++head[s];
+    out_ids[(int64_t)row * k + j] = bi;
+    out_p[(int64_t)row * k + j] = __builtin_amdgcn_exp2f(((bz - M) - logS) * LOG2E);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+struct Plan {
+  size_t off_inv_rms, off_stats, off_topv, off_topi, total;
+};
+
+bool shape_ok(const ll_shape* s, int k) {
+  if (s == nullptr) return false;
+  if (s->N < 0 || s->d <= 0 || s->V <= 0 || (s->d & 7) != 0) return false;
+  if (k < 1 || k > LL_KMAX || k > s->V) return false;
+  return true;
+}
+
+Plan make_plan(const ll_shape* s, int k) {
+  Plan p;
+  size_t off = 0;
+  p.off_inv_rms = off;
+  off = align_up(off + (size_t)s->N * sizeof(float), 256);
+  const size_t rows = (size_t)(s->N < CHUNK_ROWS ? s->N : CHUNK_ROWS);
+  p.off_stats = off;
+  off = align_up(off + rows * MAX_SPLITS * 4 * sizeof(float), 256);
+  p.off_topv = off;
+  off = align_up(off + rows * MAX_SPLITS * (size_t)k * sizeof(float), 256);
+  p.off_topi = off;
+  off = align_up(off + rows * MAX_SPLITS * (size_t)k * sizeof(int32_t), 256);
+  p.total = off;
+  return p;
+}
+
+size_t gemm_lds_bytes(int k) { return (size_t)(BM + BN) * BK * 2 + (size_t)k * BN * 8 + (size_t)QCAP * NTHREADS * 8; }
+
+int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
+                 const void* W_U, float eps, int k, const int32_t* target_ids, int32_t* out_topk_ids, float* out_topk_p,
+                 float* out_target_logp, float* out_entropy, hipStream_t stream, float* phase_ms) {
+  if (!shape_ok(shape, k)) return LL_EINVAL;
+  if (shape->N == 0) {
+    if (phase_ms) phase_ms[0] = phase_ms[1] = phase_ms[2] = 0.f;
+    return LL_OK;
+  }
+  if (hidden == nullptr || W_U == nullptr || out_topk_ids == nullptr || out_topk_p == nullptr || out_entropy == nullptr)
+    return LL_EINVAL;
+  if (target_ids != nullptr && out_target_logp == nullptr) return LL_EINVAL;
+  if (!(eps >= 0.f)) return LL_EINVAL;
+  const uintptr_t align_or = (uintptr_t)hidden | (uintptr_t)W_U | (uintptr_t)gamma;
+  if (align_or & 15) return LL_EINVAL;
+  const Plan plan = make_plan(shape, k);
+  if (workspace == nullptr || workspace_bytes < plan.total || ((uintptr_t)workspace & 255)) return LL_EWORKSPACE;
+
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  float* inv_rms = reinterpret_cast<float*>(ws + plan.off_inv_rms);
+  float* stats = reinterpret_cast<float*>(ws + plan.off_stats);
+  float* topv = reinterpret_cast<float*>(ws + plan.off_topv);
+  int32_t* topi = reinterpret_cast<int32_t*>(ws + plan.off_topi);
+
+  const int64_t N = shape->N;
+  const int d = shape->d, V = shape->V;
+  const bool fused = gamma != nullptr;
+  const size_t lds = gemm_lds_bytes(k);
+  auto kern = fused ? ll_lens_gemm_kernel<true> : ll_lens_gemm_kernel<false>;
+  LL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  if (phase_ms) {
+    phase_ms[0] = phase_ms[1] = phase_ms[2] = 0.f;
+    for (int i = 0; i < 4; ++i) LL_HIP_CHECK(hipEventCreate(&ev[i]));
+  }
+  auto finish = [&](int rc) {
+    for (int i = 0; i < 4; ++i)
+      if (ev[i]) (void)hipEventDestroy(ev[i]);
+    return rc;
+  };
+
+  // a2 for all rows at once (4 bytes of workspace per row).
+  if (phase_ms) LL_HIP_CHECK(hipEventRecord(ev[0], stream));
+  if (fused) {
+    const int64_t blocks = (N + 3) / 4;
+    hipLaunchKernelGGL(ll_rms_stats_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       static_cast<const uint16_t*>(hidden), N, d, eps, inv_rms);
+    LL_HIP_CHECK(hipGetLastError());
+  }
+  if (phase_ms) {
+    LL_HIP_CHECK(hipEventRecord(ev[1], stream));
+    LL_HIP_CHECK(hipEventSynchronize(ev[1]));
+    float ms = 0.f;
+    LL_HIP_CHECK(hipEventElapsedTime(&ms, ev[0], ev[1]));
+    phase_ms[0] += ms;
+  }
+
+  const int tiles = (V + BM - 1) / BM;
+  for (int64_t r0 = 0; r0 < N; r0 += CHUNK_ROWS) {
+    const int rows = (int)((N - r0) < CHUNK_ROWS ? (N - r0) : CHUNK_ROWS);
+    const int row_blocks = (rows + BN - 1) / BN;
+    int splits = NUM_CU / row_blocks;
+    if (splits > MAX_SPLITS) splits = MAX_SPLITS;
+    if (splits > tiles) splits = tiles;
+    if (splits < 1) splits = 1;
+    GemmArgs a;
+    a.A = static_cast<const uint16_t*>(hidden) + r0 * d;
+    a.inv_rms = fused ? inv_rms + r0 : nullptr;
+    a.gamma = static_cast<const uint16_t*>(gamma);
+    a.W = static_cast<const uint16_t*>(W_U);
+    a.target = target_ids ? target_ids + r0 : nullptr;
+    a.stats = stats;
+    a.topv = topv;
+    a.topi = topi;
+    a.rows = rows;
+    a.d = d;
+    a.V = V;
+    a.k = k;
+    a.splits = splits;
+    a.tiles = tiles;
+    a.row_blocks = row_blocks;
+    const int grid = (row_blocks * splits + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+    if (phase_ms) LL_HIP_CHECK(hipEventRecord(ev[1], stream));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHREADS), lds, stream, a);
+    LL_HIP_CHECK(hipGetLastError());
+    if (phase_ms) LL_HIP_CHECK(hipEventRecord(ev[2], stream));
+    hipLaunchKernelGGL(ll_merge_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, stats, topv, topi, rows, splits, k, V,
+                       a.target, out_topk_ids + r0 * k, out_topk_p + r0 * k,
+                       out_target_logp ? out_target_logp + r0 : nullptr, out_entropy + r0);
+    LL_HIP_CHECK(hipGetLastError());
+    if (phase_ms) {
+      LL_HIP_CHECK(hipEventRecord(ev[3], stream));
+      LL_HIP_CHECK(hipEventSynchronize(ev[3]));
+      float ms = 0.f;
+      LL_HIP_CHECK(hipEventElapsedTime(&ms, ev[1], ev[2]));
+      phase_ms[1] += ms;
+      LL_HIP_CHECK(hipEventElapsedTime(&ms, ev[2], ev[3]));
+      phase_ms[2] += ms;
+    }
+  }
+  return finish(LL_OK);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ll_workspace_bytes(const ll_shape* shape, int k) {
+  if (!shape_ok(shape, k)) return 0;
+  if (shape->N == 0) return 256;
+  return make_plan(shape, k).total;
+}
+
+int ll_project(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
+               const void* W_U, float eps, int k, const int32_t* target_ids, int32_t* out_topk_ids, float* out_topk_p,
+               float* out_target_logp, float* out_entropy, void* stream) {
+  return project_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, eps, k, target_ids, out_topk_ids, out_topk_p,
+                      out_target_logp, out_entropy, static_cast<hipStream_t>(stream), nullptr);
+}
+
+int ll_project_timed(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
+                     const void* W_U, float eps, int k, const int32_t* target_ids, int32_t* out_topk_ids, float* out_topk_p,
+                     float* out_target_logp, float* out_entropy, void* stream, float* phase_ms) {
+  if (phase_ms == nullptr) return LL_EINVAL;
+  return project_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, eps, k, target_ids, out_topk_ids, out_topk_p,
+                      out_target_logp, out_entropy, static_cast<hipStream_t>(stream), phase_ms);
+}
+
+}  // extern "C"

@@ -1,0 +1,128 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports what include/ll.h
+declares, sizes workspaces, and rejects bad arguments before touching the device."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+from paper_2604_06483_amd import binding as LL
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ll.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ll_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"ll_project", "ll_steer_vector", "ll_steer_inject", "ll_workspace_bytes", "ll_error_string"} <= set(names)
+    L = LL.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in ll.h but not exported"
+
+
+def test_header_constants_match_binding():
+    text = open(HEADER).read()
+    for name in ("LL_OK", "LL_EINVAL", "LL_EWORKSPACE", "LL_EHIP", "LL_KMAX"):
+        m = re.search(rf"#define\s+{name}\s+(-?\d+)", text)
+        assert m and int(m.group(1)) == getattr(LL, name)
+
+
+def test_error_strings():
+    L = LL.lib()
+    seen = {L.ll_error_string(c) for c in (0, -1, -2, -3)}
+    assert len(seen) == 4 and all(s for s in seen)
+    assert L.ll_error_string(-99) == b"unknown error code"
+    assert L.ll_last_hip_error() == 0
+
+
+def test_workspace_arithmetic():
+    # invalid shapes and k give 0
+    assert LL.ll_workspace_bytes(10, 0, 100, 5) == 0
+    assert LL.ll_workspace_bytes(10, 100, 100, 5) == 0          # d not a multiple of 8
+    assert LL.ll_workspace_bytes(10, 64, 100, 0) == 0
+    assert LL.ll_workspace_bytes(10, 64, 100, LL.LL_KMAX + 1) == 0
+    assert LL.ll_workspace_bytes(10, 64, 4, 5) == 0             # k > V
+    assert LL.ll_workspace_bytes(-1, 64, 100, 5) == 0
+    assert LL.ll_workspace_bytes(0, 64, 100, 5) > 0
+    # grows with k, is bounded in N beyond one pass (only 4 bytes per extra row)
+    a = LL.ll_workspace_bytes(8192, 8192, 128256, 20)
+    b = LL.ll_workspace_bytes(121500, 8192, 128256, 20)
+    assert a % 256 == 0 and b % 256 == 0
+    assert 0 < b - a <= (121500 - 8192) * 4 + 256
+    assert LL.ll_workspace_bytes(8192, 8192, 128256, 10) < a
+    assert b < 64 * 2 ** 20                                       # "bounded workspace": tens of MB
+    assert LL.ll_steer_workspace_bytes(4096) > 0 and LL.ll_steer_workspace_bytes(4097) == 0
+
+
+def _fake(n=1 << 20):
+    return ctypes.c_void_p(n)        # a non-null, 16-byte aligned address that is never dereferenced
+
+
+def test_project_rejects_bad_arguments_without_touching_the_gpu():
+    L = LL.lib()
+    s = LL.ll_shape(16, 64, 300)
+    ok = dict(shape=s, ws=_fake(4096 * 256), wsb=1 << 30, h=_fake(), g=_fake(), w=_fake(), eps=1e-5, k=4, t=_fake(),
+              ids=_fake(), p=_fake(), lp=_fake(), e=_fake(), st=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return L.ll_project(a["shape"], a["ws"], a["wsb"], a["h"], a["g"], a["w"], a["eps"], a["k"], a["t"],
+                            a["ids"], a["p"], a["lp"], a["e"], a["st"])
+
+    assert call(shape=None) == LL.LL_EINVAL
+    assert call(h=None) == LL.LL_EINVAL
+    assert call(w=None) == LL.LL_EINVAL
+    assert call(ids=None) == LL.LL_EINVAL
+    assert call(p=None) == LL.LL_EINVAL
+    assert call(e=None) == LL.LL_EINVAL
+    assert call(lp=None) == LL.LL_EINVAL                        # target ids given but nowhere to write
+    assert call(k=0) == LL.LL_EINVAL
+    assert call(k=LL.LL_KMAX + 1) == LL.LL_EINVAL
+    assert call(k=301 if 301 <= LL.LL_KMAX else 33) == LL.LL_EINVAL
+    assert call(shape=LL.ll_shape(16, 60, 300)) == LL.LL_EINVAL   # d % 8
+    assert call(shape=LL.ll_shape(-1, 64, 300)) == LL.LL_EINVAL
+    assert call(shape=LL.ll_shape(16, 64, 3)) == LL.LL_EINVAL     # k > V
+    assert call(eps=float("nan")) == LL.LL_EINVAL
+    assert call(eps=-1.0) == LL.LL_EINVAL
+    assert call(h=_fake((1 << 20) + 2)) == LL.LL_EINVAL           # misaligned
+    assert call(ws=None) == LL.LL_EWORKSPACE
+    assert call(wsb=1024) == LL.LL_EWORKSPACE
+    assert call(ws=_fake((1 << 20) + 16)) == LL.LL_EWORKSPACE     # not 256-byte aligned
+    # N == 0 succeeds with nothing else looked at
+    assert call(shape=LL.ll_shape(0, 64, 300), h=None, w=None, ws=None, wsb=0) == LL.LL_OK
+    ms = (ctypes.c_float * 3)()
+    a = ok
+    assert L.ll_project_timed(a["shape"], a["ws"], a["wsb"], a["h"], a["g"], a["w"], a["eps"], a["k"], a["t"],
+                              a["ids"], a["p"], a["lp"], a["e"], a["st"], None) == LL.LL_EINVAL
+
+
+def test_steer_calls_reject_bad_arguments():
+    L = LL.lib()
+    f = _fake()
+    assert L.ll_steer_vector(None, 4, f, 4, 64, 1, f, None, 0, None) == LL.LL_EINVAL
+    assert L.ll_steer_vector(f, 0, f, 4, 64, 1, f, None, 0, None) == LL.LL_EINVAL
+    assert L.ll_steer_vector(f, 4, f, 4, 60, 1, f, None, 0, None) == LL.LL_EINVAL
+    assert L.ll_steer_vector(f, 4, f, 4, 64, 1, None, None, 0, None) == LL.LL_EINVAL
+    assert L.ll_steer_vector(f, 4, f, 4, 64, 1, f, f, 16, None) == LL.LL_EWORKSPACE
+    s = LL.ll_shape(4, 64, 0)
+    assert L.ll_steer_inject(None, f, f, 1e-5, f, 1.0, f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject(s, None, f, 1e-5, f, 1.0, f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject(s, f, None, 1e-5, f, 1.0, f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject(s, f, f, 1e-5, None, 1.0, f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject(s, f, f, 1e-5, f, 1.0, None, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject(LL.ll_shape(4, 63, 0), f, f, 1e-5, f, 1.0, f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject(LL.ll_shape(0, 64, 0), None, None, 1e-5, None, 1.0, None, None) == LL.LL_OK
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    h = torch.zeros(4, 64, dtype=torch.bfloat16)
+    with pytest.raises(TypeError):
+        LL.ll_project(h, h[0], torch.zeros(300, 64, dtype=torch.bfloat16), 1e-5, 3)

@@ -1,0 +1,216 @@
+"""Parity of the HIP library (through the C ABI) with the CPU oracle, on a real MI355X."""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle.lens_oracle as O
+from paper_2604_06483_amd import binding as LL
+from paper_2604_06483_amd import workloads as WL
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
+
+
+def run_project(w, k=None, gamma="w", target=True):
+    cfg = w.cfg
+    res = LL.ll_project(w.hidden, w.gamma if gamma == "w" else gamma, w.W_U, cfg.eps, k or cfg.k,
+                        w.target_ids if target else None)
+    torch.cuda.synchronize()
+    return P.to_numpy(res, has_target=target)
+
+
+def oracle_for(w, rows, k=None, gamma="w"):
+    cfg = w.cfg
+    hb = WL.bf16_bits(w.hidden.reshape(-1, cfg.d)[torch.as_tensor(rows, device=w.hidden.device)])
+    gb = WL.bf16_bits(w.gamma) if gamma == "w" else None
+    wb = WL.bf16_bits(w.W_U)
+    t = w.target_ids.cpu().numpy()[rows]
+    return P.oracle_rows(hb, gb, wb, cfg.eps, k or cfg.k, t)
+
+
+# ------------------------------------------------------------------------------------------
+# small cases, every row checked: several tiles, ragged tails in N, d and V
+# ------------------------------------------------------------------------------------------
+def test_tiny_config_all_rows():
+    say("tiny config")
+    w = WL.make_workload("tiny", DEV)
+    got = run_project(w)
+    ref = oracle_for(w, np.arange(w.cfg.N))
+    rep = P.compare(got, ref, w.cfg.k, label="tiny")
+    P.check_invariants(got, w.cfg.V, w.cfg.k, label="tiny")
+    say(f"tiny: {rep}")
+
+
+RAGGED = [
+    # name,            L,  T,   d,    V,   k, outliers
+    ("tails",          3, 100,  328, 1000,  7, 2),      # N=300: 2 row blocks; d not a multiple of 64; V: 4 tiles, last partial
+    ("one-row",        1,   1,   64,  300,  3, 0),
+    ("tiny-vocab",     2,  33,  128,  100, 32, 0),      # V < one tile, k = LL_KMAX
+    ("k-equals-V",     1,  20,   72,   24, 24, 0),
+    ("k1-d8",          2,  70,    8,  513,  1, 0),      # smallest d, V = 2 tiles + 1
+    ("many-blocks",    5, 300,  192, 2048, 10, 4),      # N=1500: 6 row blocks, 8 tiles
+    ("wide-d",         1,  96, 1096,  777, 20, 0),
+]
+
+
+@pytest.mark.parametrize("case", RAGGED, ids=[c[0] for c in RAGGED])
+def test_ragged_shapes_all_rows(case):
+    name, L, T, d, V, k, n_out = case
+    say(f"ragged {name}: N={L*T} d={d} V={V} k={k}")
+    cfg = WL.LensConfig(name, L=L, T=T, d=d, V=V, k=k, n_outliers=n_out, outlier_scale=20.0)
+    w = WL.make_workload(cfg, DEV, seed=3)
+    got = run_project(w)
+    ref = oracle_for(w, np.arange(cfg.N))
+    rep = P.compare(got, ref, k, label=name)
+    P.check_invariants(got, V, k, label=name)
+    say(f"{name}: {rep}")
+
+
+def test_large_logit_scale():
+    """W_U with std 0.3: logits of tens of nats, sharply peaked rows, entropy near zero for some."""
+    say("large logit scale")
+    cfg = WL.LensConfig("peaked", L=2, T=150, d=256, V=3000, k=8)
+    w = WL.make_workload(cfg, DEV, seed=5)
+    w.W_U = (w.W_U.float() * 15.0).to(torch.bfloat16)
+    got = run_project(w)
+    ref = oracle_for(w, np.arange(cfg.N))
+    P.compare(got, ref, cfg.k, label="peaked")
+    assert ref["entropy"].min() < 1.0
+
+
+# ------------------------------------------------------------------------------------------
+# degenerate inputs
+# ------------------------------------------------------------------------------------------
+def test_empty_input_is_a_noop():
+    say("N = 0")
+    w = WL.make_workload(WL.LensConfig("e", L=1, T=4, d=64, V=300, k=3), DEV)
+    empty = w.hidden.reshape(-1, 64)[:0]
+    ids, p, logp, ent = LL.ll_project(empty, w.gamma, w.W_U, 1e-5, 3, w.target_ids[:0])
+    torch.cuda.synchronize()
+    assert ids.shape == (0, 3) and ent.shape == (0,)
+
+
+def test_zero_rows_are_uniform_and_bad_targets_give_nan():
+    say("zero rows, out-of-range targets")
+    cfg = WL.LensConfig("z", L=1, T=70, d=128, V=700, k=6)
+    w = WL.make_workload(cfg, DEV, seed=2)
+    w.hidden[0, 5] = 0
+    w.hidden[0, 69] = 0
+    w.target_ids[3] = -1
+    w.target_ids[4] = cfg.V
+    w.target_ids[5] = cfg.V - 1
+    got = run_project(w)
+    for r in (5, 69):
+        assert list(got["topk_ids"][r]) == list(range(6))          # all logits equal: ascending id
+        np.testing.assert_allclose(got["topk_p"][r], 1.0 / cfg.V, rtol=1e-5)
+        assert abs(got["entropy"][r] - math.log(cfg.V)) < 1e-5
+    assert abs(got["target_logp"][5] + math.log(cfg.V)) < 1e-5
+    assert np.isnan(got["target_logp"][3]) and np.isnan(got["target_logp"][4])
+    ref = oracle_for(w, np.arange(cfg.N))
+    P.compare(got, ref, cfg.k, label="zero-rows")
+
+
+def test_exact_ties_break_by_ascending_id():
+    """Duplicate vocabulary rows give exactly equal logits: the smaller id must come first."""
+    say("exact ties")
+    cfg = WL.LensConfig("ties", L=1, T=64, d=128, V=600, k=8)
+    w = WL.make_workload(cfg, DEV, seed=4)
+    w.W_U[300:600] = w.W_U[0:300]                                   # id v and v+300 tie exactly (different tiles)
+    w.W_U[1] = w.W_U[0]                                             # and two neighbours in one tile
+    got = run_project(w)
+    ref = oracle_for(w, np.arange(cfg.N))
+    P.compare(got, ref, cfg.k, label="ties")
+    ids = got["topk_ids"].astype(np.int64)
+    diff = ids[:, 1:] - ids[:, :-1]
+    # a duplicated row's two ids sit next to each other (equal logits), smaller id first
+    assert np.sum(diff == 300) >= cfg.N and np.sum(diff == -300) == 0
+    for r in range(cfg.N):
+        row = list(ids[r])
+        for v in row:
+            if 1 < v < 300:
+                if v + 300 in row:
+                    assert row.index(v + 300) == row.index(v) + 1
+                else:
+                    assert row.index(v) == cfg.k - 1
+        if 0 in row and 1 in row:
+            assert row.index(0) < row.index(1)
+
+
+def test_no_target_and_prenormalised_rows():
+    say("target_ids = NULL; gamma = NULL")
+    cfg = WL.LensConfig("nt", L=2, T=80, d=256, V=900, k=5)
+    w = WL.make_workload(cfg, DEV, seed=6)
+    got = run_project(w, target=False)
+    ref = oracle_for(w, np.arange(cfg.N))
+    P.compare(got, ref, cfg.k, has_target=False, label="no-target")
+    # gamma = NULL: rows are used as they are
+    res = LL.ll_project(w.hidden, None, w.W_U, cfg.eps, cfg.k, w.target_ids)
+    torch.cuda.synchronize()
+    got = P.to_numpy(res)
+    ref = oracle_for(w, np.arange(cfg.N), gamma=None)
+    P.compare(got, ref, cfg.k, label="gamma-null")
+
+
+def test_caller_workspace_and_stream():
+    say("caller-provided workspace on a side stream, twice")
+    cfg = WL.LensConfig("ws", L=1, T=300, d=192, V=1500, k=4)
+    w = WL.make_workload(cfg, DEV, seed=7)
+    need = LL.ll_workspace_bytes(cfg.N, cfg.d, cfg.V, cfg.k)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)                                                  # stale contents must not matter
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        a = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, stream=s)
+        b = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, stream=s)
+    s.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    ref = oracle_for(w, np.arange(cfg.N))
+    P.compare(P.to_numpy(a), ref, cfg.k, label="workspace")
+    with pytest.raises(LL.LLError) as e:
+        LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws[:need - 256])
+    assert e.value.code == LL.LL_EWORKSPACE
+
+
+def test_timed_variant_matches():
+    say("ll_project_timed")
+    w = WL.make_workload("tiny", DEV)
+    a = LL.ll_project(w.hidden, w.gamma, w.W_U, 1e-5, 5, w.target_ids)
+    b = LL.ll_project(w.hidden, w.gamma, w.W_U, 1e-5, 5, w.target_ids, timed=True)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b[:4]):
+        assert torch.equal(x, y)
+    assert len(b[4]) == 3 and all(t >= 0 for t in b[4]) and b[4][1] > 0
+
+
+# ------------------------------------------------------------------------------------------
+# the paper-shaped configs at full size, in the launch configuration the benchmark times:
+# sampled rows against the oracle, every row against the invariants
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["qwen3-4b", "llama31-8b", "qwen3-32b", "llama31-70b"])
+def test_full_size_config_sampled_rows(name):
+    cfg = WL.CONFIGS[name]
+    say(f"full size {name}: N={cfg.N} d={cfg.d} V={cfg.V} k={cfg.k}")
+    w = WL.make_workload(cfg, DEV)
+    got = run_project(w)
+    P.check_invariants(got, cfg.V, cfg.k, label=name)
+    rows = WL.sample_rows(cfg, 256)
+    ref = oracle_for(w, rows)
+    rep = P.compare(P.take(got, rows), ref, cfg.k, label=name)
+    say(f"{name}: {rep}")
+    # the Gaussian unembedding predicts the mean entropy: log V - var(z)/2 (a sanity band, not the gate)
+    a = O.rmsnorm(WL.bf16_bits(w.hidden.reshape(-1, cfg.d)[torch.as_tensor(rows, device=DEV)]),
+                  WL.bf16_bits(w.gamma), cfg.eps)
+    pred = math.log(cfg.V) - 0.5 * 0.02 ** 2 * np.sum(a * a, axis=1)
+    assert abs(float(np.mean(got["entropy"][rows])) - float(np.mean(pred))) < 0.05
+    del w
+    torch.cuda.empty_cache()

@@ -1,0 +1,131 @@
+"""Steering kernels (paper Sec. 3.4, Eq. 2 and Eq. 3) against the CPU oracle, on a real MI355X."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle.lens_oracle as O
+from paper_2604_06483_amd import binding as LL
+from paper_2604_06483_amd import workloads as WL
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
+
+
+def ulp_distance(a_bits, b_bits):
+    """Distance in bf16 steps between two arrays of bf16 bit patterns (same sign assumed or zero crossing)."""
+    def key(b):
+        b = b.astype(np.int32)
+        return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+    return np.abs(key(a_bits) - key(b_bits))
+
+
+@pytest.mark.parametrize("nb,nt,d,use_ws", [(64, 64, 4096, False), (64, 64, 4096, True), (1, 1, 64, False),
+                                             (5, 130, 328, True), (700, 333, 8192, True), (40, 17, 520, False)])
+def test_steer_vector(nb, nt, d, use_ws):
+    say(f"steer_vector nb={nb} nt={nt} d={d} ws={use_ws}")
+    g = torch.Generator(device=DEV).manual_seed(nb * 1000 + nt)
+    base = (3 * torch.randn((nb, d), generator=g, device=DEV)).to(torch.bfloat16)
+    target = (3 * torch.randn((nt, d), generator=g, device=DEV) + 0.5).to(torch.bfloat16)
+    ws = torch.empty(LL.ll_steer_workspace_bytes(d), dtype=torch.uint8, device=DEV) if use_ws else None
+    for normalize in (True, False):
+        v = LL.ll_steer_vector(base, target, normalize, workspace=ws)
+        torch.cuda.synchronize()
+        want = O.steer_vector(WL.bf16_bits(base), WL.bf16_bits(target), normalize)
+        scale = np.abs(want).max()
+        np.testing.assert_allclose(v.cpu().numpy(), want, rtol=0, atol=2e-6 * scale * max(1, (nb + nt) ** 0.5))
+        if normalize:
+            assert abs(float((v.double() ** 2).sum()) - 1.0) < 1e-5
+
+
+def test_steer_vector_zero_difference():
+    say("steer_vector zero difference")
+    base = torch.randn((8, 256), device=DEV).to(torch.bfloat16)
+    v = LL.ll_steer_vector(base, base.clone(), True)
+    torch.cuda.synchronize()
+    assert torch.all(v == 0)
+
+
+@pytest.mark.parametrize("N,d", [(300, 4096), (7, 328), (130, 8192), (33, 64), (20, 9000)])
+def test_steer_inject(N, d):
+    say(f"steer_inject N={N} d={d}")
+    cfg = WL.LensConfig("inj", L=1, T=N, d=d, V=64, k=1, n_outliers=min(4, d // 16), outlier_scale=20.0)
+    w = WL.make_workload(cfg, DEV, seed=9)
+    g = torch.Generator(device=DEV).manual_seed(1)
+    v = torch.randn((d,), generator=g, device=DEV)
+    v = v / v.norm()
+    hb, gb = WL.bf16_bits(w.hidden.reshape(N, d)), WL.bf16_bits(w.gamma)
+    for alpha in (0.0, 2.5, -4.0):
+        out = LL.ll_steer_inject(w.hidden, w.gamma, cfg.eps, v, alpha)
+        torch.cuda.synchronize()
+        got = WL.bf16_bits(out.reshape(N, d))
+        want = O.steer_inject(hb, gb, cfg.eps, v.cpu().numpy(), alpha)
+        dist = ulp_distance(got, want)
+        # fp32 arithmetic before the one bf16 rounding: a result may sit on the other side of a rounding
+        # boundary when the exact value is within a few fp32 ulps of it -> rare one-step differences only
+        assert dist.max() <= 1, f"alpha={alpha}: {dist.max()} bf16 steps apart"
+        assert (dist != 0).mean() < 2e-3, f"alpha={alpha}: {(dist != 0).mean():.2e} of elements differ"
+    # in place
+    h2 = w.hidden.clone()
+    LL.ll_steer_inject(h2, w.gamma, cfg.eps, v, 2.5, out=h2)
+    ref = LL.ll_steer_inject(w.hidden, w.gamma, cfg.eps, v, 2.5)
+    torch.cuda.synchronize()
+    assert torch.equal(h2, ref)
+
+
+def test_alpha_zero_is_the_identity():
+    """Injecting with alpha = 0 and projecting the result with gamma = NULL equals projecting the raw rows."""
+    say("alpha = 0 identity")
+    cfg = WL.LensConfig("id", L=2, T=200, d=512, V=3000, k=10, n_outliers=4, outlier_scale=20.0)
+    w = WL.make_workload(cfg, DEV, seed=11)
+    v = torch.randn((cfg.d,), device=DEV)
+    a = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids)
+    h0 = LL.ll_steer_inject(w.hidden, w.gamma, cfg.eps, v, 0.0)
+    b = LL.ll_project(h0, None, w.W_U, cfg.eps, cfg.k, w.target_ids)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_config3_alpha_sweep():
+    """LLaMA-3.1-8B-shaped steering run: direction from 64 + 64 label-position rows, injected into the
+    middle layer's 1500 rows with alpha in {-4..4}, each projected; sampled rows against the oracle."""
+    cfg = WL.CONFIGS["llama31-8b"]
+    say("config-3 alpha sweep")
+    w = WL.make_workload(cfg, DEV)
+    base, target, l_star = WL.make_steer_rows(cfg, w.outlier_idx, DEV)
+    v = LL.ll_steer_vector(base, target, True)
+    torch.cuda.synchronize()
+    v_ref = O.steer_vector(WL.bf16_bits(base), WL.bf16_bits(target))
+    np.testing.assert_allclose(v.cpu().numpy(), v_ref, atol=1e-6)
+    layer = w.hidden[l_star].contiguous()                          # [T, d]
+    wb, gb = WL.bf16_bits(w.W_U), WL.bf16_bits(w.gamma)
+    rows = np.array([0, 1, 37, 640, 1023, 1024, 1498, 1499])
+    hb = WL.bf16_bits(layer)[rows]
+    # the token that W_U v favours most: its log-prob must rise with alpha
+    tok = int(torch.argmax(w.W_U.float() @ v))
+    tgt = torch.full((cfg.T,), tok, dtype=torch.int32, device=DEV)
+    curve = []
+    for alpha in range(-4, 5):
+        say(f"  alpha={alpha}")
+        h1 = LL.ll_steer_inject(layer, w.gamma, cfg.eps, v, float(alpha))
+        res = LL.ll_project(h1, None, w.W_U, cfg.eps, cfg.k, tgt)
+        torch.cuda.synchronize()
+        got = P.to_numpy(res)
+        P.check_invariants(got, cfg.V, cfg.k, label=f"alpha={alpha}")
+        # oracle: inject with the library's own fp32 v (v itself was checked above), then project
+        h1_ref = O.steer_inject(hb, gb, cfg.eps, v.cpu().numpy(), float(alpha))
+        ref = P.oracle_rows(h1_ref, None, wb, cfg.eps, cfg.k, np.full(len(rows), tok))
+        # the library's injected rows may differ from the oracle's by one bf16 step in rare elements;
+        # project the library's own rows through the oracle for the gate
+        ref_own = P.oracle_rows(WL.bf16_bits(h1)[rows], None, wb, cfg.eps, cfg.k, np.full(len(rows), tok))
+        P.compare(P.take(got, rows), ref_own, cfg.k, label=f"alpha={alpha}")
+        assert np.max(np.abs(ref_own["target_logp"] - ref["target_logp"])) < 5e-3
+        curve.append(got["target_logp"].mean())
+    assert np.all(np.diff(curve) > 0), curve
