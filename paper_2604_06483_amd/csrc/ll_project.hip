@@ -9,6 +9,7 @@
 #include <math.h>
 
 #include <type_traits>
+#include <vector>
 
 namespace {
 
@@ -432,32 +433,36 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   auto kern = fused ? ll_lens_gemm_kernel<true> : ll_lens_gemm_kernel<false>;
   LL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
 
-  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
-  if (phase_ms) {
-    phase_ms[0] = phase_ms[1] = phase_ms[2] = 0.f;
-    for (int i = 0; i < 4; ++i) LL_HIP_CHECK(hipEventCreate(&ev[i]));
-  }
+  // Timing (ll_project_timed only): events are recorded in-stream around every kernel and read
+  // after one synchronisation at the end, so the kernels run back to back as in ll_project.
+  std::vector<hipEvent_t> ev;
+  auto mark = [&]() -> hipError_t {
+    if (!phase_ms) return hipSuccess;
+    hipEvent_t e = nullptr;
+    hipError_t rc = hipEventCreate(&e);
+    if (rc != hipSuccess) return rc;
+    ev.push_back(e);
+    return hipEventRecord(e, stream);
+  };
   auto finish = [&](int rc) {
-    for (int i = 0; i < 4; ++i)
-      if (ev[i]) (void)hipEventDestroy(ev[i]);
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
     return rc;
   };
+#define LL_CHECK_F(expr)                                   \
+  do {                                                     \
+    hipError_t e__ = (expr);                               \
+    if (e__ != hipSuccess) return finish(hip_failed(e__)); \
+  } while (0)
 
   // a2 for all rows at once (4 bytes of workspace per row).
-  if (phase_ms) LL_HIP_CHECK(hipEventRecord(ev[0], stream));
+  LL_CHECK_F(mark());
   if (fused) {
     const int64_t blocks = (N + 3) / 4;
     hipLaunchKernelGGL(ll_rms_stats_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
                        static_cast<const uint16_t*>(hidden), N, d, eps, inv_rms);
-    LL_HIP_CHECK(hipGetLastError());
+    LL_CHECK_F(hipGetLastError());
   }
-  if (phase_ms) {
-    LL_HIP_CHECK(hipEventRecord(ev[1], stream));
-    LL_HIP_CHECK(hipEventSynchronize(ev[1]));
-    float ms = 0.f;
-    LL_HIP_CHECK(hipEventElapsedTime(&ms, ev[0], ev[1]));
-    phase_ms[0] += ms;
-  }
+  LL_CHECK_F(mark());
 
   const int tiles = (V + BM - 1) / BM;
   for (int64_t r0 = 0; r0 < N; r0 += CHUNK_ROWS) {
@@ -484,24 +489,30 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     a.tiles = tiles;
     a.row_blocks = row_blocks;
     const int grid = (row_blocks * splits + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
-    if (phase_ms) LL_HIP_CHECK(hipEventRecord(ev[1], stream));
+    LL_CHECK_F(mark());
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHREADS), lds, stream, a);
-    LL_HIP_CHECK(hipGetLastError());
-    if (phase_ms) LL_HIP_CHECK(hipEventRecord(ev[2], stream));
+    LL_CHECK_F(hipGetLastError());
+    LL_CHECK_F(mark());
     hipLaunchKernelGGL(ll_merge_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, stats, topv, topi, rows, splits, k, V,
                        a.target, out_topk_ids + r0 * k, out_topk_p + r0 * k,
                        out_target_logp ? out_target_logp + r0 : nullptr, out_entropy + r0);
-    LL_HIP_CHECK(hipGetLastError());
-    if (phase_ms) {
-      LL_HIP_CHECK(hipEventRecord(ev[3], stream));
-      LL_HIP_CHECK(hipEventSynchronize(ev[3]));
-      float ms = 0.f;
-      LL_HIP_CHECK(hipEventElapsedTime(&ms, ev[1], ev[2]));
+    LL_CHECK_F(hipGetLastError());
+    LL_CHECK_F(mark());
+  }
+  if (phase_ms) {
+    LL_CHECK_F(hipStreamSynchronize(stream));
+    float ms = 0.f;
+    LL_CHECK_F(hipEventElapsedTime(&ms, ev[0], ev[1]));
+    phase_ms[0] = ms;
+    phase_ms[1] = phase_ms[2] = 0.f;
+    for (size_t i = 2; i + 2 < ev.size(); i += 3) {
+      LL_CHECK_F(hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
       phase_ms[1] += ms;
-      LL_HIP_CHECK(hipEventElapsedTime(&ms, ev[2], ev[3]));
+      LL_CHECK_F(hipEventElapsedTime(&ms, ev[i + 1], ev[i + 2]));
       phase_ms[2] += ms;
     }
   }
+#undef LL_CHECK_F
   return finish(LL_OK);
 }
 
