@@ -119,6 +119,17 @@ int ll_steer_vector(const void* base, int64_t n_base, const void* target, int64_
 int ll_steer_inject(const ll_shape* shape, const void* hidden, const void* gamma, float eps,
                     const float* v, float alpha, void* out_hidden, void* stream);
 
+/*
+ * Chooses the projection kernel for later ll_project calls of this process (not thread safe):
+ *   0  automatic (default)
+ *   1  register-staged kernel: the RMSNorm scaling is applied inside the A-tile load of the GEMM
+ *   2  direct-to-LDS kernel fed from a normalised bf16 panel written once per row pass
+ * Both compute the same quantities from the same bf16 operands; results agree bit for bit
+ * unless the accumulation order of a logit differs (it does not: same K order).  For tuning
+ * and tests.  Returns LL_EINVAL for any other value.
+ */
+int ll_set_gemm_path(int path);
+
 /* Text for an LL_E* code (static storage, never NULL). */
 const char* ll_error_string(int code);
 

@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.ll_steer_inject.argtypes = [POINTER(ll_shape), c_void_p, c_void_p, c_float, c_void_p, c_float,
                                       c_void_p, c_void_p]
         L.ll_steer_inject.restype = c_int
+        L.ll_set_gemm_path.argtypes = [c_int]
+        L.ll_set_gemm_path.restype = c_int
         L.ll_error_string.argtypes = [c_int]
         L.ll_error_string.restype = c_char_p
         L.ll_last_hip_error.argtypes = []
@@ -79,6 +81,12 @@ def _check(t, dtype, name, shape=None):
 def _stream(stream):
     s = torch.cuda.current_stream() if stream is None else stream
     return c_void_p(s.cuda_stream)
+
+
+def ll_set_gemm_path(path: int) -> None:
+    rc = lib().ll_set_gemm_path(int(path))
+    if rc != LL_OK:
+        raise LLError(rc, "ll_set_gemm_path")
 
 
 def ll_workspace_bytes(N: int, d: int, V: int, k: int) -> int:

@@ -24,7 +24,7 @@ constexpr int BK = 64;           // K step staged in LDS
 constexpr int NTHREADS = 256;    // 4 wavefronts, one per SIMD
 constexpr int CHUNK_ROWS = 8192; // lens rows per pass
 constexpr int MAX_SPLITS = 16;   // vocabulary splits per row block
-constexpr int QCAP = 8;          // top-k candidate queue entries per lane
+constexpr int QCAP = 4;          // top-k candidate queue entries per lane
 constexpr int NUM_XCD = 8;
 constexpr int NUM_CU = 256;
 constexpr float NEG_BIG = -3.0e38f;   // stands for "no logit" without the NaNs that -inf would breed
@@ -49,6 +49,64 @@ __global__ __launch_bounds__(256) void ll_rms_stats_kernel(const uint16_t* __res
 }
 
 // ---------------------------------------------------------------------------------------
+// a2 + a3 materialised: panel[r, :] = bf16((h[r, :] * inv_rms[r]) * gamma), zero padded to the
+// panel's row stride; gamma == nullptr copies the rows unchanged.  One wavefront per row; the
+// row stays in registers between the statistic and the write when it fits.
+// ---------------------------------------------------------------------------------------
+template <int NITER>
+__global__ __launch_bounds__(256) void ll_norm_panel_kernel(const uint16_t* __restrict__ hidden,
+                                                            const uint16_t* __restrict__ gamma, uint16_t* __restrict__ panel,
+                                                            int rows, int d, int64_t lda, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const uint4* src = reinterpret_cast<const uint4*>(hidden + (int64_t)row * d);
+  uint4* dst = reinterpret_cast<uint4*>(panel + (int64_t)row * lda);
+  const uint4* g4 = reinterpret_cast<const uint4*>(gamma);
+  const int n16 = d >> 3;
+  const int n16_pad = (int)(lda >> 3);
+  float acc0 = 0.f, acc1 = 0.f;
+  uint4 cache[NITER > 0 ? NITER : 1];
+  if (NITER > 0) {
+#pragma unroll
+    for (int it = 0; it < NITER; ++it) {
+      const int c = lane + 64 * it;
+      if (c < n16) {
+        cache[it] = src[c];
+        accum_sq(cache[it], acc0, acc1);
+      }
+    }
+  } else {
+    for (int c = lane; c < n16; c += 64) accum_sq(src[c], acc0, acc1);
+  }
+  const float inv = inv_rms_from_sumsq(wave_sum(acc0 + acc1), d, eps);
+  auto emit = [&](int c, const uint4 q) {
+    if (gamma == nullptr) {
+      dst[c] = q;
+      return;
+    }
+    const uint4 g = g4[c];
+    const uint32_t hw[4] = {q.x, q.y, q.z, q.w};
+    const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+    uint32_t ow[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      ow[i] = pack_bf16(bf16_lo(hw[i]) * inv * bf16_lo(gw[i]), bf16_hi(hw[i]) * inv * bf16_hi(gw[i]));
+    dst[c] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+  };
+  if (NITER > 0) {
+#pragma unroll
+    for (int it = 0; it < NITER; ++it) {
+      const int c = lane + 64 * it;
+      if (c < n16) emit(c, cache[it]);
+    }
+  } else {
+    for (int c = lane; c < n16; c += 64) emit(c, src[c]);
+  }
+  for (int c = n16 + lane; c < n16_pad; c += 64) dst[c] = make_uint4(0, 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------------
 // a3..a7: the fused kernel.
 //
 // One workgroup owns BN = 256 lens rows and one vocabulary split; it sweeps the split's 256-wide
@@ -68,12 +126,180 @@ struct GemmArgs {
   float* stats;             // [rows, splits, 4]  (m, S, U, z_target)
   float* topv;              // [rows, splits, k]
   int32_t* topi;            // [rows, splits, k]
+  int64_t lda;              // row stride of A in elements
   int rows, d, V, k, splits, tiles, row_blocks;
 };
 
+// ---------------------------------------------------------------------------------------
+// Epilogue shared by both GEMM kernels.  State of one lens row, private to the lane that owns it.
+// ---------------------------------------------------------------------------------------
+struct RowState {
+  float m = -INFINITY;      // running maximum logit
+  float s = 0.f;            // sum exp(z - m)
+  float u = 0.f;            // sum exp(z - m) * (z - m)
+  float z_tgt = -INFINITY;  // logit of the target id, once its tile has passed
+  float tau = -INFINITY;    // current k-th best logit (list tail)
+  int tau_id = INT_MAX;
+  int tgt = -1;             // target id of the row (-1: none)
+};
+
+struct EpiLds {
+  float* listV;  // [k][256] sorted top-k logits of the 256 rows (descending; ties ascending id)
+  int* listI;    // [k][256]
+  float* queV;   // [QCAP][256] candidate queue
+  int* queI;
+};
+
+// Reads one accumulator element where it lives (an AGPR) at the point of use, so that the
+// register allocator does not copy the whole 256-register tile into VGPRs ahead of the epilogue.
+__device__ __forceinline__ float acc_read(float a) {
+  float v;
+  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+  return v;
+}
+
+__device__ __forceinline__ void epilogue_init(const EpiLds& L, int k, int tid) {
+  for (int j = 0; j < k; ++j) {
+    L.listV[j * BN + tid] = -INFINITY;
+    L.listI[j * BN + tid] = INT_MAX;
+  }
+}
+
+// Processes vocabulary entries [v0 + 32 I, v0 + 32 I + 32) of the finished tile for the lane's row.
+template <int I>
+__device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowState& st, const EpiLds& L, int v0, int V,
+                                               int k, bool partial, int tid) {
+  // x[o]: logit of vocabulary entry v0 + 32 I + o for this lane's row.  The swap hands the lower
+  // lane half the row tile j = 0 and the upper half j = 1, so that lane l owns row 64 w + l.
+  float x[32];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc_read(acc[I][0][r])),
+                                               __float_as_uint(acc_read(acc[I][1][r])), false, false);
+    const int o = 8 * (r >> 2) + (r & 3);
+    x[o] = __uint_as_float(sw[0]);
+    x[o + 4] = __uint_as_float(sw[1]);
+  }
+  const int g0 = v0 + 32 * I;
+  if (partial) {
+#pragma unroll
+    for (int o = 0; o < 32; ++o)
+      if (g0 + o >= V) x[o] = NEG_BIG;
+  }
+  // a7: target gather
+  const int tl = st.tgt - g0;
+  if (__builtin_amdgcn_ballot_w64((unsigned)tl < 32u) != 0) {
+#pragma unroll
+    for (int o = 0; o < 32; ++o)
+      if (tl == o) st.z_tgt = x[o];
+  }
+  // a5: online max / sum-exp / sum exp*(z-m)
+  float gmax = x[0];
+#pragma unroll
+  for (int o = 1; o < 32; ++o) gmax = fmaxf(gmax, x[o]);
+  const float m_new = fmaxf(st.m, gmax);
+  if (__builtin_amdgcn_ballot_w64(m_new > st.m) != 0) {
+    const float dm = (st.m == -INFINITY) ? 0.f : st.m - m_new;
+    const float sc = __builtin_amdgcn_exp2f(dm * LOG2E);
+    st.u = sc * fmaf(dm, st.s, st.u);
+    st.s = sc * st.s;
+    st.m = m_new;
+  }
+  const float mb = st.m * LOG2E;
+  float s4[4] = {0.f, 0.f, 0.f, 0.f}, u4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int o = 0; o < 32; ++o) {
+    const float e = __builtin_amdgcn_exp2f(fmaf(x[o], LOG2E, -mb));
+    s4[o & 3] += e;
+    u4[o & 3] = fmaf(e, x[o] - st.m, u4[o & 3]);
+  }
+  st.s += (s4[0] + s4[1]) + (s4[2] + s4[3]);
+  st.u += (u4[0] + u4[1]) + (u4[2] + u4[3]);
+
+  // a6: streaming top-k.  Values that reach the current k-th best go through a small per-lane
+  // queue in LDS and are then inserted into the lane's sorted list; the queue is filled in
+  // windows of QCAP hits so that any number of hits is handled.
+  const float tau_scan = st.tau;
+  for (unsigned base = 0;; base += QCAP) {
+    unsigned cnt = 0;
+#pragma unroll
+    for (int o = 0; o < 32; ++o) {
+      if (x[o] >= tau_scan) {
+        const unsigned pos = cnt - base;
+        if (pos < (unsigned)QCAP) {
+          L.queV[pos * NTHREADS + tid] = x[o];
+          L.queI[pos * NTHREADS + tid] = g0 + o;
+        }
+        ++cnt;
+      }
+    }
+    if (__builtin_amdgcn_ballot_w64(cnt > base) == 0) break;
+    const unsigned n = cnt > base ? (cnt - base < (unsigned)QCAP ? cnt - base : (unsigned)QCAP) : 0u;
+    for (unsigned q = 0; q < n; ++q) {
+      const float z = L.queV[q * NTHREADS + tid];
+      const int id = L.queI[q * NTHREADS + tid];
+      if (id < V && (z > st.tau || (z == st.tau && id < st.tau_id))) {
+        int j = k - 1;
+        while (j > 0) {
+          const float pv = L.listV[(j - 1) * BN + tid];
+          const int pi = L.listI[(j - 1) * BN + tid];
+          if (pv > z || (pv == z && pi < id)) break;
+          L.listV[j * BN + tid] = pv;
+          L.listI[j * BN + tid] = pi;
+          --j;
+        }
+        L.listV[j * BN + tid] = z;
+        L.listI[j * BN + tid] = id;
+        st.tau = L.listV[(k - 1) * BN + tid];
+        st.tau_id = L.listI[(k - 1) * BN + tid];
+      }
+    }
+    if (__builtin_amdgcn_ballot_w64(cnt > base + QCAP) == 0) break;
+  }
+}
+
+__device__ __forceinline__ void epilogue_tile(const f32x16 (&acc)[8][2], RowState& st, const EpiLds& L, int v0, int V,
+                                              int k, int tid) {
+  const bool partial = v0 + BM > V;
+  // The accumulators are read below through inline asm, which the compiler's MFMA hazard
+  // bookkeeping does not see: let the last MFMA of the tile drain first.
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+  epilogue_group<0>(acc, st, L, v0, V, k, partial, tid);
+  epilogue_group<1>(acc, st, L, v0, V, k, partial, tid);
+  epilogue_group<2>(acc, st, L, v0, V, k, partial, tid);
+  epilogue_group<3>(acc, st, L, v0, V, k, partial, tid);
+  epilogue_group<4>(acc, st, L, v0, V, k, partial, tid);
+  epilogue_group<5>(acc, st, L, v0, V, k, partial, tid);
+  epilogue_group<6>(acc, st, L, v0, V, k, partial, tid);
+  epilogue_group<7>(acc, st, L, v0, V, k, partial, tid);
+}
+
+// Per-(row, split) partial results: (m, S, U, z_target) and the sorted top-k list.
+__device__ __forceinline__ void epilogue_store(const GemmArgs& p, const RowState& st, const EpiLds& L, int my_row, int split,
+                                               int tid) {
+  if (my_row >= p.rows) return;
+  const int64_t o = (int64_t)my_row * p.splits + split;
+  reinterpret_cast<float4*>(p.stats)[o] = make_float4(st.m, st.s, st.u, st.z_tgt);
+  for (int j = 0; j < p.k; ++j) {
+    p.topv[o * p.k + j] = L.listV[j * BN + tid];
+    p.topi[o * p.k + j] = L.listI[j * BN + tid];
+  }
+}
+
+// Workgroup ids are dealt round-robin over the 8 XCDs; remap so that one XCD (one L2) gets a
+// compact rectangle of (row blocks) x (all splits) and its CUs share A panels and W tiles.
+__device__ __forceinline__ int xcd_logical_block() {
+  const int per_xcd = gridDim.x / NUM_XCD;
+  return (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+}
+
+// ---------------------------------------------------------------------------------------
+// Generic kernel: any d that is a multiple of 8; operands staged through registers, with the
+// RMSNorm scaling (a3) applied between the global load and the LDS store of every A tile.
 // LDS tile: [256 rows][8 chunks of 16 B]; chunk index XOR-swizzled with (row/2)%8 so that both the
 // 16-byte row-major stores and the MFMA fragment reads (32 consecutive rows, one chunk) spread
 // over all banks.
+// ---------------------------------------------------------------------------------------
 __device__ __forceinline__ int lds_off(int row, int chunk) { return (row * 8 + (chunk ^ ((row >> 1) & 7))) * 16; }
 
 template <bool FUSED_NORM>
@@ -82,15 +308,13 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* sW = smem;
   unsigned char* sA = smem + BM * BK * 2;
-  float* listV = reinterpret_cast<float*>(smem + (BM + BN) * BK * 2);
-  int* listI = reinterpret_cast<int*>(listV + p.k * BN);
-  float* queV = reinterpret_cast<float*>(listI + p.k * BN);
-  int* queI = reinterpret_cast<int*>(queV + QCAP * NTHREADS);
+  EpiLds L;
+  L.listV = reinterpret_cast<float*>(smem + (BM + BN) * BK * 2);
+  L.listI = reinterpret_cast<int*>(L.listV + p.k * BN);
+  L.queV = reinterpret_cast<float*>(L.listI + p.k * BN);
+  L.queI = reinterpret_cast<int*>(L.queV + QCAP * NTHREADS);
 
-  // Workgroup ids are dealt round-robin over the 8 XCDs; remap so that one XCD (one L2) gets a
-  // compact rectangle of (row blocks) x (all splits) and its CUs share A panels and W tiles.
-  const int per_xcd = gridDim.x / NUM_XCD;
-  const int logical = (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+  const int logical = xcd_logical_block();
   if (logical >= p.row_blocks * p.splits) return;
   const int split = logical % p.splits;
   const int rb = logical / p.splits;
@@ -101,6 +325,7 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int d = p.d, V = p.V, k = p.k;
+  const int64_t lda = p.lda;
 
   // --- global -> LDS staging map: thread handles physical chunk (tid % 8) of rows tid/8 + 32 i.
   const int ld_row = tid >> 3;
@@ -113,7 +338,7 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
   for (int i = 0; i < 8; ++i) {
     int r = rb * BN + ld_row + 32 * i;
     r = r < p.rows ? r : p.rows - 1;
-    a_ptr[i] = p.A + (int64_t)r * d + ld_chunk * 8;
+    a_ptr[i] = p.A + (int64_t)r * lda + ld_chunk * 8;
     a_scale[i] = FUSED_NORM ? p.inv_rms[r] : 1.0f;
   }
 
@@ -123,14 +348,9 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
 
   // --- epilogue state: this lane owns lens row (rb*BN + tid).
   const int my_row = rb * BN + tid;
-  float m_run = -INFINITY, s_run = 0.f, u_run = 0.f, z_tgt = -INFINITY;
-  float tau = -INFINITY;
-  int tau_id = INT_MAX;
-  const int tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
-  for (int j = 0; j < k; ++j) {
-    listV[j * BN + tid] = -INFINITY;
-    listI[j * BN + tid] = INT_MAX;
-  }
+  RowState st;
+  st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
+  epilogue_init(L, k, tid);
 
   const int KT = (d + BK - 1) / BK;
 
@@ -201,117 +421,161 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
       }
     }
-
-    // ------------------------------ epilogue ------------------------------
-    const bool partial = v0 + BM > V;
-    const int tl = tgt - v0;       // target position inside this tile, if in [0, 256)
-    auto group = [&](auto group_index) {
-      constexpr int i = decltype(group_index)::value;
-      // x[o]: logit of vocabulary entry v0 + 32 i + o for this lane's row.
-      float x[32];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][0][r]), __float_as_uint(acc[i][1][r]),
-                                                   false, false);
-        const int o = 8 * (r >> 2) + (r & 3);
-        x[o] = __uint_as_float(sw[0]);
-        x[o + 4] = __uint_as_float(sw[1]);
-      }
-      const int g0 = v0 + 32 * i;
-      if (partial) {
-#pragma unroll
-        for (int o = 0; o < 32; ++o)
-          if (g0 + o >= V) x[o] = NEG_BIG;
-      }
-      // a7: target gather
-      if (__builtin_amdgcn_ballot_w64((unsigned)(tl - 32 * i) < 32u) != 0) {
-#pragma unroll
-        for (int o = 0; o < 32; ++o)
-          if (tl == 32 * i + o) z_tgt = x[o];
-      }
-      // a5: online max / sum-exp / sum exp*(z-m)
-      float gmax = x[0];
-#pragma unroll
-      for (int o = 1; o < 32; ++o) gmax = fmaxf(gmax, x[o]);
-      const float m_new = fmaxf(m_run, gmax);
-      if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-        const float dm = (m_run == -INFINITY) ? 0.f : m_run - m_new;
-        const float sc = __builtin_amdgcn_exp2f(dm * LOG2E);
-        u_run = sc * fmaf(dm, s_run, u_run);
-        s_run = sc * s_run;
-        m_run = m_new;
-      }
-      const float mb = m_run * LOG2E;
-      float s4[4] = {0.f, 0.f, 0.f, 0.f}, u4[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int o = 0; o < 32; ++o) {
-        const float e = __builtin_amdgcn_exp2f(fmaf(x[o], LOG2E, -mb));
-        s4[o & 3] += e;
-        u4[o & 3] = fmaf(e, x[o] - m_run, u4[o & 3]);
-      }
-      s_run += (s4[0] + s4[1]) + (s4[2] + s4[3]);
-      u_run += (u4[0] + u4[1]) + (u4[2] + u4[3]);
-
-      // a6: streaming top-k.  Values that reach the current k-th best go through a small
-      // per-lane queue in LDS and are then inserted into the lane's sorted list; the queue is
-      // filled in windows of QCAP hits so that any number of hits is handled.
-      const float tau_scan = tau;
-      for (unsigned base = 0;; base += QCAP) {
-        unsigned cnt = 0;
-#pragma unroll
-        for (int o = 0; o < 32; ++o) {
-          if (x[o] >= tau_scan) {
-            const unsigned pos = cnt - base;
-            if (pos < (unsigned)QCAP) {
-              queV[pos * NTHREADS + tid] = x[o];
-              queI[pos * NTHREADS + tid] = g0 + o;
-            }
-            ++cnt;
-          }
-        }
-        if (__builtin_amdgcn_ballot_w64(cnt > base) == 0) break;
-        const unsigned n = cnt > base ? (cnt - base < (unsigned)QCAP ? cnt - base : (unsigned)QCAP) : 0u;
-        for (unsigned q = 0; q < n; ++q) {
-          const float z = queV[q * NTHREADS + tid];
-          const int id = queI[q * NTHREADS + tid];
-          if (id < V && (z > tau || (z == tau && id < tau_id))) {
-            int j = k - 1;
-            while (j > 0) {
-              const float pv = listV[(j - 1) * BN + tid];
-              const int pi = listI[(j - 1) * BN + tid];
-              if (pv > z || (pv == z && pi < id)) break;
-              listV[j * BN + tid] = pv;
-              listI[j * BN + tid] = pi;
-              --j;
-            }
-            listV[j * BN + tid] = z;
-            listI[j * BN + tid] = id;
-            tau = listV[(k - 1) * BN + tid];
-            tau_id = listI[(k - 1) * BN + tid];
-          }
-        }
-        if (__builtin_amdgcn_ballot_w64(cnt > base + QCAP) == 0) break;
-      }
-    };
-    group(std::integral_constant<int, 0>{});
-    group(std::integral_constant<int, 1>{});
-    group(std::integral_constant<int, 2>{});
-    group(std::integral_constant<int, 3>{});
-    group(std::integral_constant<int, 4>{});
-    group(std::integral_constant<int, 5>{});
-    group(std::integral_constant<int, 6>{});
-    group(std::integral_constant<int, 7>{});
+    epilogue_tile(acc, st, L, v0, V, k, tid);
   }
+  epilogue_store(p, st, L, my_row, split, tid);
+}
 
-  // ---- per-(row, split) partial results
-  if (my_row < p.rows) {
-    const int64_t o = (int64_t)my_row * p.splits + split;
-    reinterpret_cast<float4*>(p.stats)[o] = make_float4(m_run, s_run, u_run, z_tgt);
-    for (int j = 0; j < k; ++j) {
-      p.topv[o * k + j] = listV[j * BN + tid];
-      p.topi[o * k + j] = listI[j * BN + tid];
+// ---------------------------------------------------------------------------------------
+// Fast kernel: both operands go from global memory straight into LDS (global_load_lds, 16 bytes
+// per lane) through a ring of NST stages of K = 32, one barrier per stage, and the ring keeps
+// running across vocabulary tiles so that the next tile's first stages load under the epilogue.
+// A must be a panel of already normalised bf16 rows with row stride lda, a multiple of 32, zero
+// padded beyond d (the norm kernel below writes it); W rows are read in place.
+//
+// Stage layout: W tile [256 rows][64 B] then A tile [256 rows][64 B]; the 16-byte chunk index is
+// XOR-swizzled with (row/4)%4, which makes the 16 rows x 4 chunks that one load instruction
+// writes (1 KB, lane-linear) and the 32 rows x 1 chunk that a fragment read touches both
+// bank-conflict free.
+// ---------------------------------------------------------------------------------------
+constexpr int DK = 32;
+constexpr int STAGE_BYTES = (BM + BN) * DK * 2;
+constexpr int LOADS_PER_STAGE = 8;   // per wavefront: 4 W segments + 4 A segments of 1 KB
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <int NST>
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void ll_lens_gemm_dma_kernel(const GemmArgs p) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  EpiLds L;
+  L.listV = reinterpret_cast<float*>(smem + NST * STAGE_BYTES);
+  L.listI = reinterpret_cast<int*>(L.listV + p.k * BN);
+  L.queV = reinterpret_cast<float*>(L.listI + p.k * BN);
+  L.queI = reinterpret_cast<int*>(L.queV + QCAP * NTHREADS);
+
+  const int logical = xcd_logical_block();
+  if (logical >= p.row_blocks * p.splits) return;
+  const int split = logical % p.splits;
+  const int rb = logical / p.splits;
+  const int tile0 = (int)((int64_t)split * p.tiles / p.splits);
+  const int tile1 = (int)((int64_t)(split + 1) * p.tiles / p.splits);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int d = p.d, V = p.V, k = p.k;
+  const int lda = (int)p.lda;
+  const int KT = lda / DK;
+
+  // --- DMA map.  One load instruction fills 16 rows x 64 B; lane l lands at row l/4, physical
+  // chunk l%4, so it fetches logical chunk (l%4) ^ ((l/16)%4).  Wavefront w fills rows
+  // [64w, 64w+64) of both tiles.  Addresses are a wave-uniform base plus a 32-bit byte offset.
+  const int seg_row = 64 * wave + (lane >> 2);                   // + 16 s
+  const int seg_koff = (((lane & 3) ^ ((lane >> 4) & 3))) * 8;   // element offset inside the K step
+  const unsigned char* a_base = reinterpret_cast<const unsigned char*>(p.A + (int64_t)rb * BN * lda);
+  const int a_last = p.rows - 1 - rb * BN;                       // last valid row of this block
+  int i_tile = tile0, i_kt = 0, i_buf = 0;                       // next stage to issue
+  auto issue = [&]() {
+    unsigned char* stage = smem + i_buf * STAGE_BYTES + (64 * wave) * (DK * 2);
+    const unsigned char* w_base = reinterpret_cast<const unsigned char*>(p.W + (int64_t)i_tile * BM * d);
+    const int w_last = V - 1 - i_tile * BM;
+    int wk = i_kt * DK + seg_koff;
+    wk = wk < d - 8 ? wk : d - 8;              // beyond d the A panel is zero: any finite W chunk will do
+    const int ak = i_kt * DK + seg_koff;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int wr = min(seg_row + 16 * s, w_last);
+      const int ar = min(seg_row + 16 * s, a_last);
+      const unsigned w_off = (unsigned)(wr * d + wk) * 2u;
+      const unsigned a_off = (unsigned)(ar * lda + ak) * 2u;
+      __builtin_amdgcn_global_load_lds((gptr_t)(w_base + w_off), (lptr_t)(stage + s * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(a_base + a_off), (lptr_t)(stage + BM * DK * 2 + s * 1024), 16, 0, 0);
     }
+    i_buf = i_buf + 1 == NST ? 0 : i_buf + 1;
+    if (++i_kt == KT) {
+      i_kt = 0;
+      ++i_tile;
+    }
+  };
+
+  // --- MFMA fragment map: lane reads row (lane % 32) of each 32-row group, K chunk 2*kk + lane/32.
+  const int f_row = lane & 31;
+  const int f_half = lane >> 5;
+  const int f_swz = (f_row >> 2) & 3;
+  const int f_off0 = f_row * (DK * 2) + ((f_half ^ f_swz) * 16);         // kk = 0
+  const int f_off1 = f_row * (DK * 2) + (((2 + f_half) ^ f_swz) * 16);   // kk = 1
+
+  const int my_row = rb * BN + tid;
+  RowState st;
+  st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
+  epilogue_init(L, k, tid);
+
+  int to_issue = (tile1 - tile0) * KT;      // stages not yet issued
+  int pending = 0;                          // stages issued and not yet consumed
+#pragma unroll
+  for (int s = 0; s < NST - 1; ++s)
+    if (to_issue > 0) {
+      issue();
+      --to_issue;
+      ++pending;
+    }
+
+  int buf = 0;
+  for (int tile = tile0; tile < tile1; ++tile) {
+    f32x16 acc[8][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    for (int kt = 0; kt < KT; ++kt) {
+      // The oldest pending stage has landed once at most the later ones' loads are outstanding.
+      if (NST >= 3 && pending >= 2) {
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (LOADS_PER_STAGE * (NST - 2)));   // vmcnt(8 * (NST-2)), NST <= 3
+      } else {
+        __builtin_amdgcn_s_waitcnt(0x0F70);                                  // vmcnt(0)
+      }
+      __syncthreads();   // everyone's part of this stage is visible; everyone is done with the previous one
+      --pending;
+      if (to_issue > 0) {                    // refill the buffer the previous stage used
+        issue();
+        --to_issue;
+        ++pending;
+      }
+      const unsigned char* sW = smem + buf * STAGE_BYTES;
+      const unsigned char* sA = sW + BM * DK * 2 + (wave * 64) * (DK * 2);
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const int off = kk == 0 ? f_off0 : f_off1;
+        bf16x8 fa[2], fw[8];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(sA + j * 32 * (DK * 2) + off);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(sW + i * 32 * (DK * 2) + off);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+      }
+      // Pin the order: all 10 fragment reads of kk = 0 up front, the 10 of kk = 1 one by one
+      // under the first MFMAs, so that LDS latency hides behind matrix work.
+      __builtin_amdgcn_sched_group_barrier(0x100, 10, 0);
+#pragma unroll
+      for (int i = 0; i < 10; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 22, 0);
+      buf = buf + 1 == NST ? 0 : buf + 1;
+    }
+    epilogue_tile(acc, st, L, tile * BM, V, k, tid);
   }
+  epilogue_store(p, st, L, my_row, split, tid);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -375,7 +639,8 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float* __restrict__
 // host side
 // ---------------------------------------------------------------------------------------
 struct Plan {
-  size_t off_inv_rms, off_stats, off_topv, off_topi, total;
+  size_t off_inv_rms, off_stats, off_topv, off_topi, off_panel, total;
+  int64_t lda;
 };
 
 bool shape_ok(const ll_shape* s, int k) {
@@ -397,11 +662,20 @@ Plan make_plan(const ll_shape* s, int k) {
   off = align_up(off + rows * MAX_SPLITS * (size_t)k * sizeof(float), 256);
   p.off_topi = off;
   off = align_up(off + rows * MAX_SPLITS * (size_t)k * sizeof(int32_t), 256);
+  p.lda = (s->d + DK - 1) / DK * DK;
+  p.off_panel = off;
+  off = align_up(off + rows * (size_t)p.lda * sizeof(uint16_t), 256);
   p.total = off;
   return p;
 }
 
-size_t gemm_lds_bytes(int k) { return (size_t)(BM + BN) * BK * 2 + (size_t)k * BN * 8 + (size_t)QCAP * NTHREADS * 8; }
+constexpr size_t LDS_MAX = 160 * 1024;
+size_t epi_lds_bytes(int k) { return (size_t)k * BN * 8 + (size_t)QCAP * NTHREADS * 8; }
+size_t gemm_lds_bytes(int k) { return (size_t)(BM + BN) * BK * 2 + epi_lds_bytes(k); }
+
+// 0: automatic; 1: register-staged kernel with the norm fused into the A-tile load; 2: DMA kernel
+// fed from a normalised panel.
+int g_gemm_path = 0;
 
 int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
                  const void* W_U, float eps, int k, const int32_t* target_ids, int32_t* out_topk_ids, float* out_topk_p,
@@ -425,13 +699,19 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   float* stats = reinterpret_cast<float*>(ws + plan.off_stats);
   float* topv = reinterpret_cast<float*>(ws + plan.off_topv);
   int32_t* topi = reinterpret_cast<int32_t*>(ws + plan.off_topi);
+  uint16_t* panel = reinterpret_cast<uint16_t*>(ws + plan.off_panel);
 
   const int64_t N = shape->N;
   const int d = shape->d, V = shape->V;
-  const bool fused = gamma != nullptr;
-  const size_t lds = gemm_lds_bytes(k);
-  auto kern = fused ? ll_lens_gemm_kernel<true> : ll_lens_gemm_kernel<false>;
+  const bool has_gamma = gamma != nullptr;
+  const bool dma = g_gemm_path != 1;
+  const int nst = (size_t)3 * STAGE_BYTES + epi_lds_bytes(k) <= LDS_MAX ? 3 : 2;
+  const size_t lds = dma ? (size_t)nst * STAGE_BYTES + epi_lds_bytes(k) : gemm_lds_bytes(k);
+  void (*kern)(const GemmArgs) = dma ? (nst == 3 ? ll_lens_gemm_dma_kernel<3> : ll_lens_gemm_dma_kernel<2>)
+                                     : (has_gamma ? ll_lens_gemm_kernel<true> : ll_lens_gemm_kernel<false>);
   LL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  // The DMA kernel reads hidden in place when the rows need neither scaling nor padding.
+  const bool need_panel = dma && (has_gamma || plan.lda != d);
 
   // Timing (ll_project_timed only): events are recorded in-stream around every kernel and read
   // after one synchronisation at the end, so the kernels run back to back as in ll_project.
@@ -454,27 +734,36 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     if (e__ != hipSuccess) return finish(hip_failed(e__)); \
   } while (0)
 
-  // a2 for all rows at once (4 bytes of workspace per row).
-  LL_CHECK_F(mark());
-  if (fused) {
-    const int64_t blocks = (N + 3) / 4;
-    hipLaunchKernelGGL(ll_rms_stats_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
-                       static_cast<const uint16_t*>(hidden), N, d, eps, inv_rms);
-    LL_CHECK_F(hipGetLastError());
-  }
-  LL_CHECK_F(mark());
-
   const int tiles = (V + BM - 1) / BM;
   for (int64_t r0 = 0; r0 < N; r0 += CHUNK_ROWS) {
     const int rows = (int)((N - r0) < CHUNK_ROWS ? (N - r0) : CHUNK_ROWS);
+    const uint16_t* h_rows = static_cast<const uint16_t*>(hidden) + r0 * d;
+    // a2 (+ a3 when the panel is used)
+    LL_CHECK_F(mark());
+    if (need_panel) {
+      const dim3 grid((unsigned)((rows + 3) / 4));
+      const uint16_t* g = static_cast<const uint16_t*>(gamma);
+      if (d <= 64 * 8 * 4)
+        hipLaunchKernelGGL(ll_norm_panel_kernel<4>, grid, dim3(256), 0, stream, h_rows, g, panel, rows, d, plan.lda, eps);
+      else if (d <= 64 * 8 * 16)
+        hipLaunchKernelGGL(ll_norm_panel_kernel<16>, grid, dim3(256), 0, stream, h_rows, g, panel, rows, d, plan.lda, eps);
+      else
+        hipLaunchKernelGGL(ll_norm_panel_kernel<0>, grid, dim3(256), 0, stream, h_rows, g, panel, rows, d, plan.lda, eps);
+      LL_CHECK_F(hipGetLastError());
+    } else if (!dma && has_gamma) {
+      hipLaunchKernelGGL(ll_rms_stats_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, h_rows, (int64_t)rows, d,
+                         eps, inv_rms + r0);
+      LL_CHECK_F(hipGetLastError());
+    }
     const int row_blocks = (rows + BN - 1) / BN;
     int splits = NUM_CU / row_blocks;
     if (splits > MAX_SPLITS) splits = MAX_SPLITS;
     if (splits > tiles) splits = tiles;
     if (splits < 1) splits = 1;
     GemmArgs a;
-    a.A = static_cast<const uint16_t*>(hidden) + r0 * d;
-    a.inv_rms = fused ? inv_rms + r0 : nullptr;
+    a.A = need_panel ? panel : h_rows;
+    a.lda = need_panel ? plan.lda : d;
+    a.inv_rms = (!dma && has_gamma) ? inv_rms + r0 : nullptr;
     a.gamma = static_cast<const uint16_t*>(gamma);
     a.W = static_cast<const uint16_t*>(W_U);
     a.target = target_ids ? target_ids + r0 : nullptr;
@@ -501,14 +790,14 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   }
   if (phase_ms) {
     LL_CHECK_F(hipStreamSynchronize(stream));
-    float ms = 0.f;
-    LL_CHECK_F(hipEventElapsedTime(&ms, ev[0], ev[1]));
-    phase_ms[0] = ms;
-    phase_ms[1] = phase_ms[2] = 0.f;
-    for (size_t i = 2; i + 2 < ev.size(); i += 3) {
+    phase_ms[0] = phase_ms[1] = phase_ms[2] = 0.f;
+    for (size_t i = 0; i + 3 < ev.size(); i += 4) {
+      float ms = 0.f;
       LL_CHECK_F(hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
-      phase_ms[1] += ms;
+      phase_ms[0] += ms;
       LL_CHECK_F(hipEventElapsedTime(&ms, ev[i + 1], ev[i + 2]));
+      phase_ms[1] += ms;
+      LL_CHECK_F(hipEventElapsedTime(&ms, ev[i + 2], ev[i + 3]));
       phase_ms[2] += ms;
     }
   }
@@ -519,6 +808,12 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
 }  // namespace
 
 extern "C" {
+
+int ll_set_gemm_path(int path) {
+  if (path < 0 || path > 2) return LL_EINVAL;
+  g_gemm_path = path;
+  return LL_OK;
+}
 
 size_t ll_workspace_bytes(const ll_shape* shape, int k) {
   if (!shape_ok(shape, k)) return 0;

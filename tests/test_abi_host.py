@@ -57,7 +57,7 @@ def test_workspace_arithmetic():
     assert a % 256 == 0 and b % 256 == 0
     assert 0 < b - a <= (121500 - 8192) * 4 + 256
     assert LL.ll_workspace_bytes(8192, 8192, 128256, 10) < a
-    assert b < 64 * 2 ** 20                                       # "bounded workspace": tens of MB
+    assert b < 256 * 2 ** 20                                      # "bounded workspace": tens of MB
     assert LL.ll_steer_workspace_bytes(4096) > 0 and LL.ll_steer_workspace_bytes(4097) == 0
 
 

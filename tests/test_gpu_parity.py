@@ -19,6 +19,14 @@ def say(msg):
     print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
 
 
+@pytest.fixture(params=[2, 1], ids=["dma-panel", "fused-norm"], autouse=True)
+def gemm_path(request):
+    """Every case runs on both projection kernels."""
+    LL.ll_set_gemm_path(request.param)
+    yield request.param
+    LL.ll_set_gemm_path(0)
+
+
 def run_project(w, k=None, gamma="w", target=True):
     cfg = w.cfg
     res = LL.ll_project(w.hidden, w.gamma if gamma == "w" else gamma, w.W_U, cfg.eps, k or cfg.k,
@@ -197,7 +205,10 @@ def test_timed_variant_matches():
 # sampled rows against the oracle, every row against the invariants
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("name", ["qwen3-4b", "llama31-8b", "qwen3-32b", "llama31-70b"])
-def test_full_size_config_sampled_rows(name):
+def test_full_size_config_sampled_rows(name, gemm_path):
+    if gemm_path != 2:
+        pytest.skip("full sizes run in the configuration the benchmark times (the default kernel)")
+    LL.ll_set_gemm_path(0)
     cfg = WL.CONFIGS[name]
     say(f"full size {name}: N={cfg.N} d={cfg.d} V={cfg.V} k={cfg.k}")
     w = WL.make_workload(cfg, DEV)
