@@ -1,5 +1,6 @@
-// Fused logit-lens projection for gfx950: RMS statistics, bf16 MFMA GEMM over the vocabulary with
-// an online-softmax / top-k / target-gather epilogue, and the merge of the vocabulary splits.
+// Fused logit-lens projection for gfx950: RMS statistics / normalised panel, bf16 MFMA GEMM over
+// the vocabulary with an online-softmax / top-k / target-gather epilogue, and the merge of the
+// vocabulary splits.
 //
 // Follows the paper's Sec. 3.3 (Eq. 1 and "Top-k extraction") and Alg. 1 Phase 2; the logits of
 // Eq. 1 live only in MFMA accumulators.
@@ -20,11 +21,10 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int BM = 256;          // vocabulary rows per tile (MFMA M side)
 constexpr int BN = 256;          // lens rows per workgroup (MFMA N side)
-constexpr int BK = 64;           // K step staged in LDS
+constexpr int BK = 64;           // K step of the register-staged kernel
 constexpr int NTHREADS = 256;    // 4 wavefronts, one per SIMD
 constexpr int CHUNK_ROWS = 8192; // lens rows per pass
 constexpr int MAX_SPLITS = 16;   // vocabulary splits per row block
-constexpr int QCAP = 4;          // top-k candidate queue entries per lane
 constexpr int NUM_XCD = 8;
 constexpr int NUM_CU = 256;
 constexpr float NEG_BIG = -3.0e38f;   // stands for "no logit" without the NaNs that -inf would breed
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void ll_norm_panel_kernel(const uint16_t* __re
 }
 
 // ---------------------------------------------------------------------------------------
-// a3..a7: the fused kernel.
+// a3..a7: the fused kernels.
 //
 // One workgroup owns BN = 256 lens rows and one vocabulary split; it sweeps the split's 256-wide
 // vocabulary tiles.  Per tile the logits Z^T[vocab, row] = W_tile . A^T are accumulated with
@@ -118,37 +118,35 @@ __global__ __launch_bounds__(256) void ll_norm_panel_kernel(const uint16_t* __re
 // wavefront w holds all 256 logits of lens row 64w + l, so the whole epilogue is lane-private.
 // ---------------------------------------------------------------------------------------
 struct GemmArgs {
-  const uint16_t* A;        // [rows, d] bf16 (this pass's rows)
+  const uint16_t* A;        // [rows, lda] bf16 (this pass's rows)
   const float* inv_rms;     // [rows] or nullptr (rows already normalised)
   const uint16_t* gamma;    // [d] or nullptr
   const uint16_t* W;        // [V, d] bf16
   const int32_t* target;    // [rows] or nullptr
-  float* stats;             // [rows, splits, 4]  (m, S, U, z_target)
-  float* topv;              // [rows, splits, k]
-  int32_t* topi;            // [rows, splits, k]
+  float4* stats;            // [rows, splits]     (m, S, T, z_target)
+  uint2* top;               // [rows, splits, k]  (logit bits, id), sorted
   int64_t lda;              // row stride of A in elements
   int rows, d, V, k, splits, tiles, row_blocks;
 };
 
 // ---------------------------------------------------------------------------------------
 // Epilogue shared by both GEMM kernels.  State of one lens row, private to the lane that owns it.
+// With m the running maximum: S = sum exp(z - m), T = sum exp(z - m) z.  Then
+// logsumexp = m + log S and entropy = m + log S - T / S.
 // ---------------------------------------------------------------------------------------
 struct RowState {
-  float m = -INFINITY;      // running maximum logit
-  float s = 0.f;            // sum exp(z - m)
-  float u = 0.f;            // sum exp(z - m) * (z - m)
+  float m = -INFINITY;
+  float s = 0.f;
+  float t = 0.f;
   float z_tgt = -INFINITY;  // logit of the target id, once its tile has passed
   float tau = -INFINITY;    // current k-th best logit (list tail)
   int tau_id = INT_MAX;
   int tgt = -1;             // target id of the row (-1: none)
 };
 
-struct EpiLds {
-  float* listV;  // [k][256] sorted top-k logits of the 256 rows (descending; ties ascending id)
-  int* listI;    // [k][256]
-  float* queV;   // [QCAP][256] candidate queue
-  int* queI;
-};
+// Sorted top-k lists of the workgroup's 256 rows in LDS: entry j of row r at [j][r] as
+// (logit bits, id); descending logit, ascending id among equal logits.
+typedef uint2* TopLists;
 
 // Reads one accumulator element where it lives (an AGPR) at the point of use, so that the
 // register allocator does not copy the whole 256-register tile into VGPRs ahead of the epilogue.
@@ -158,16 +156,77 @@ __device__ __forceinline__ float acc_read(float a) {
   return v;
 }
 
-__device__ __forceinline__ void epilogue_init(const EpiLds& L, int k, int tid) {
-  for (int j = 0; j < k; ++j) {
-    L.listV[j * BN + tid] = -INFINITY;
-    L.listI[j * BN + tid] = INT_MAX;
+__device__ __forceinline__ void epilogue_init(TopLists list, int k, int tid) {
+  for (int j = 0; j < k; ++j) list[j * BN + tid] = make_uint2(__float_as_uint(-INFINITY), (unsigned)INT_MAX);
+}
+
+// true if list entry e ranks above the candidate (z, id)
+__device__ __forceinline__ bool ranks_above(const uint2 e, float z, int id) {
+  const float ev = __uint_as_float(e.x);
+  return ev > z || (ev == z && (int)e.y < id);
+}
+
+// Inserts (z, id), which is known to rank above the current tail, into the lane's sorted list.
+// Walks up from the tail four entries at a time so that the LDS round trips overlap.
+__device__ __forceinline__ void topk_insert(TopLists list, int k, int tid, float z, int id, RowState& st) {
+  const uint2 cand = make_uint2(__float_as_uint(z), (unsigned)id);
+  uint2* col = list + tid;
+  int j = k - 1;                 // slot the candidate would take if nothing above it moves
+  uint2 new_tail = cand;
+  bool first = true;
+  while (j > 0) {
+    const uint2 e1 = col[(j - 1) * BN];
+    const uint2 e2 = col[(j >= 2 ? j - 2 : 0) * BN];
+    const uint2 e3 = col[(j >= 3 ? j - 3 : 0) * BN];
+    const uint2 e4 = col[(j >= 4 ? j - 4 : 0) * BN];
+    if (ranks_above(e1, z, id)) break;
+    if (first) new_tail = e1;    // the old second-to-last entry becomes the tail
+    first = false;
+    col[j * BN] = e1;
+    if (j < 2 || ranks_above(e2, z, id)) { j -= 1; break; }
+    col[(j - 1) * BN] = e2;
+    if (j < 3 || ranks_above(e3, z, id)) { j -= 2; break; }
+    col[(j - 2) * BN] = e3;
+    if (j < 4 || ranks_above(e4, z, id)) { j -= 3; break; }
+    col[(j - 3) * BN] = e4;
+    j -= 4;
   }
+  col[j * BN] = cand;
+  st.tau = __uint_as_float(new_tail.x);
+  st.tau_id = (int)new_tail.y;
+}
+
+// x[o] for a per-lane o in [0, 32): registers cannot be indexed by a lane-varying position, so
+// pick through a binary tree of 31 selects.  The selects are written as instructions because the
+// optimiser would otherwise fold the tree back into an indexed access and move the 32 values
+// to scratch memory.
+__device__ __forceinline__ float cndmask(float if_clear, float if_set, unsigned long long lanes) {
+  float r;
+  asm("v_cndmask_b32 %0, %1, %2, %3" : "=v"(r) : "v"(if_clear), "v"(if_set), "s"(lanes));
+  return r;
+}
+
+__device__ __forceinline__ float select32(const float (&x)[32], int o) {
+  const unsigned long long b0 = __builtin_amdgcn_ballot_w64((o & 1) != 0);
+  const unsigned long long b1 = __builtin_amdgcn_ballot_w64((o & 2) != 0);
+  const unsigned long long b2 = __builtin_amdgcn_ballot_w64((o & 4) != 0);
+  const unsigned long long b3 = __builtin_amdgcn_ballot_w64((o & 8) != 0);
+  const unsigned long long b4 = __builtin_amdgcn_ballot_w64((o & 16) != 0);
+  float a[16], b[8], c[4], e[2];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) a[i] = cndmask(x[2 * i], x[2 * i + 1], b0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) b[i] = cndmask(a[2 * i], a[2 * i + 1], b1);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) c[i] = cndmask(b[2 * i], b[2 * i + 1], b2);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) e[i] = cndmask(c[2 * i], c[2 * i + 1], b3);
+  return cndmask(e[0], e[1], b4);
 }
 
 // Processes vocabulary entries [v0 + 32 I, v0 + 32 I + 32) of the finished tile for the lane's row.
 template <int I>
-__device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowState& st, const EpiLds& L, int v0, int V,
+__device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowState& st, TopLists list, int v0, int V,
                                                int k, bool partial, int tid) {
   // x[o]: logit of vocabulary entry v0 + 32 I + o for this lane's row.  The swap hands the lower
   // lane half the row tile j = 0 and the upper half j = 1, so that lane l owns row 64 w + l.
@@ -193,97 +252,68 @@ __device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowSta
     for (int o = 0; o < 32; ++o)
       if (tl == o) st.z_tgt = x[o];
   }
-  // a5: online max / sum-exp / sum exp*(z-m)
+  // a5: online max / sum exp / sum exp * z
   float gmax = x[0];
 #pragma unroll
   for (int o = 1; o < 32; ++o) gmax = fmaxf(gmax, x[o]);
   const float m_new = fmaxf(st.m, gmax);
   if (__builtin_amdgcn_ballot_w64(m_new > st.m) != 0) {
-    const float dm = (st.m == -INFINITY) ? 0.f : st.m - m_new;
-    const float sc = __builtin_amdgcn_exp2f(dm * LOG2E);
-    st.u = sc * fmaf(dm, st.s, st.u);
-    st.s = sc * st.s;
+    const float sc = __builtin_amdgcn_exp2f((st.m - m_new) * LOG2E);   // first group: exp2(-inf) = 0
+    st.s *= sc;
+    st.t *= sc;
     st.m = m_new;
   }
   const float mb = st.m * LOG2E;
-  float s4[4] = {0.f, 0.f, 0.f, 0.f}, u4[4] = {0.f, 0.f, 0.f, 0.f};
+  float s4[4] = {0.f, 0.f, 0.f, 0.f}, t4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int o = 0; o < 32; ++o) {
     const float e = __builtin_amdgcn_exp2f(fmaf(x[o], LOG2E, -mb));
     s4[o & 3] += e;
-    u4[o & 3] = fmaf(e, x[o] - st.m, u4[o & 3]);
+    t4[o & 3] = fmaf(e, x[o], t4[o & 3]);
   }
   st.s += (s4[0] + s4[1]) + (s4[2] + s4[3]);
-  st.u += (u4[0] + u4[1]) + (u4[2] + u4[3]);
+  st.t += (t4[0] + t4[1]) + (t4[2] + t4[3]);
 
-  // a6: streaming top-k.  Values that reach the current k-th best go through a small per-lane
-  // queue in LDS and are then inserted into the lane's sorted list; the queue is filled in
-  // windows of QCAP hits so that any number of hits is handled.
-  const float tau_scan = st.tau;
-  for (unsigned base = 0;; base += QCAP) {
-    unsigned cnt = 0;
+  // a6: streaming top-k.  Only when some lane of the wavefront has a logit that reaches its
+  // current k-th best: mark the candidates against the threshold, then insert them one by one
+  // (the exact comparison against the moving tail happens at insertion).
+  if (__builtin_amdgcn_ballot_w64(gmax >= st.tau) != 0) {
+    unsigned mask = 0;
 #pragma unroll
-    for (int o = 0; o < 32; ++o) {
-      if (x[o] >= tau_scan) {
-        const unsigned pos = cnt - base;
-        if (pos < (unsigned)QCAP) {
-          L.queV[pos * NTHREADS + tid] = x[o];
-          L.queI[pos * NTHREADS + tid] = g0 + o;
-        }
-        ++cnt;
-      }
+    for (int o = 0; o < 32; ++o) mask |= (x[o] >= st.tau ? 1u : 0u) << o;
+    while (mask != 0) {
+      const int o = __builtin_ctz(mask);
+      mask &= mask - 1;
+      const float z = select32(x, o);
+      const int id = g0 + o;
+      if (id < V && (z > st.tau || (z == st.tau && id < st.tau_id))) topk_insert(list, k, tid, z, id, st);
     }
-    if (__builtin_amdgcn_ballot_w64(cnt > base) == 0) break;
-    const unsigned n = cnt > base ? (cnt - base < (unsigned)QCAP ? cnt - base : (unsigned)QCAP) : 0u;
-    for (unsigned q = 0; q < n; ++q) {
-      const float z = L.queV[q * NTHREADS + tid];
-      const int id = L.queI[q * NTHREADS + tid];
-      if (id < V && (z > st.tau || (z == st.tau && id < st.tau_id))) {
-        int j = k - 1;
-        while (j > 0) {
-          const float pv = L.listV[(j - 1) * BN + tid];
-          const int pi = L.listI[(j - 1) * BN + tid];
-          if (pv > z || (pv == z && pi < id)) break;
-          L.listV[j * BN + tid] = pv;
-          L.listI[j * BN + tid] = pi;
-          --j;
-        }
-        L.listV[j * BN + tid] = z;
-        L.listI[j * BN + tid] = id;
-        st.tau = L.listV[(k - 1) * BN + tid];
-        st.tau_id = L.listI[(k - 1) * BN + tid];
-      }
-    }
-    if (__builtin_amdgcn_ballot_w64(cnt > base + QCAP) == 0) break;
   }
 }
 
-__device__ __forceinline__ void epilogue_tile(const f32x16 (&acc)[8][2], RowState& st, const EpiLds& L, int v0, int V,
+__device__ __forceinline__ void epilogue_tile(const f32x16 (&acc)[8][2], RowState& st, TopLists list, int v0, int V,
                                               int k, int tid) {
   const bool partial = v0 + BM > V;
   // The accumulators are read below through inline asm, which the compiler's MFMA hazard
   // bookkeeping does not see: let the last MFMA of the tile drain first.
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-  epilogue_group<0>(acc, st, L, v0, V, k, partial, tid);
-  epilogue_group<1>(acc, st, L, v0, V, k, partial, tid);
-  epilogue_group<2>(acc, st, L, v0, V, k, partial, tid);
-  epilogue_group<3>(acc, st, L, v0, V, k, partial, tid);
-  epilogue_group<4>(acc, st, L, v0, V, k, partial, tid);
-  epilogue_group<5>(acc, st, L, v0, V, k, partial, tid);
-  epilogue_group<6>(acc, st, L, v0, V, k, partial, tid);
-  epilogue_group<7>(acc, st, L, v0, V, k, partial, tid);
+  epilogue_group<0>(acc, st, list, v0, V, k, partial, tid);
+  epilogue_group<1>(acc, st, list, v0, V, k, partial, tid);
+  epilogue_group<2>(acc, st, list, v0, V, k, partial, tid);
+  epilogue_group<3>(acc, st, list, v0, V, k, partial, tid);
+  epilogue_group<4>(acc, st, list, v0, V, k, partial, tid);
+  epilogue_group<5>(acc, st, list, v0, V, k, partial, tid);
+  epilogue_group<6>(acc, st, list, v0, V, k, partial, tid);
+  epilogue_group<7>(acc, st, list, v0, V, k, partial, tid);
 }
 
-// Per-(row, split) partial results: (m, S, U, z_target) and the sorted top-k list.
-__device__ __forceinline__ void epilogue_store(const GemmArgs& p, const RowState& st, const EpiLds& L, int my_row, int split,
+// Per-(row, split) partial results: (m, S, T, z_target) and the sorted top-k list.
+__device__ __forceinline__ void epilogue_store(const GemmArgs& p, const RowState& st, TopLists list, int my_row, int split,
                                                int tid) {
   if (my_row >= p.rows) return;
   const int64_t o = (int64_t)my_row * p.splits + split;
-  reinterpret_cast<float4*>(p.stats)[o] = make_float4(st.m, st.s, st.u, st.z_tgt);
-  for (int j = 0; j < p.k; ++j) {
-    p.topv[o * p.k + j] = L.listV[j * BN + tid];
-    p.topi[o * p.k + j] = L.listI[j * BN + tid];
-  }
+  p.stats[o] = make_float4(st.m, st.s, st.t, st.z_tgt);
+  for (int j = 0; j < p.k; ++j) p.top[o * p.k + j] = list[j * BN + tid];
 }
 
 // Workgroup ids are dealt round-robin over the 8 XCDs; remap so that one XCD (one L2) gets a
@@ -294,8 +324,8 @@ __device__ __forceinline__ int xcd_logical_block() {
 }
 
 // ---------------------------------------------------------------------------------------
-// Generic kernel: any d that is a multiple of 8; operands staged through registers, with the
-// RMSNorm scaling (a3) applied between the global load and the LDS store of every A tile.
+// Register-staged kernel: any d that is a multiple of 8; operands go global -> registers -> LDS,
+// with the RMSNorm scaling (a3) applied between the global load and the LDS store of every A tile.
 // LDS tile: [256 rows][8 chunks of 16 B]; chunk index XOR-swizzled with (row/2)%8 so that both the
 // 16-byte row-major stores and the MFMA fragment reads (32 consecutive rows, one chunk) spread
 // over all banks.
@@ -308,11 +338,7 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* sW = smem;
   unsigned char* sA = smem + BM * BK * 2;
-  EpiLds L;
-  L.listV = reinterpret_cast<float*>(smem + (BM + BN) * BK * 2);
-  L.listI = reinterpret_cast<int*>(L.listV + p.k * BN);
-  L.queV = reinterpret_cast<float*>(L.listI + p.k * BN);
-  L.queI = reinterpret_cast<int*>(L.queV + QCAP * NTHREADS);
+  TopLists list = reinterpret_cast<uint2*>(smem + (BM + BN) * BK * 2);
 
   const int logical = xcd_logical_block();
   if (logical >= p.row_blocks * p.splits) return;
@@ -350,7 +376,7 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
   const int my_row = rb * BN + tid;
   RowState st;
   st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
-  epilogue_init(L, k, tid);
+  epilogue_init(list, k, tid);
 
   const int KT = (d + BK - 1) / BK;
 
@@ -421,39 +447,48 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
       }
     }
-    epilogue_tile(acc, st, L, v0, V, k, tid);
+    epilogue_tile(acc, st, list, v0, V, k, tid);
   }
-  epilogue_store(p, st, L, my_row, split, tid);
+  epilogue_store(p, st, list, my_row, split, tid);
 }
 
 // ---------------------------------------------------------------------------------------
-// Fast kernel: both operands go from global memory straight into LDS (global_load_lds, 16 bytes
-// per lane) through a ring of NST stages of K = 32, one barrier per stage, and the ring keeps
-// running across vocabulary tiles so that the next tile's first stages load under the epilogue.
-// A must be a panel of already normalised bf16 rows with row stride lda, a multiple of 32, zero
-// padded beyond d (the norm kernel below writes it); W rows are read in place.
+// Direct-to-LDS kernel: both operands go from global memory straight into LDS (global_load_lds,
+// 16 bytes per lane) through a ring of 3 stages of K = 32.  A must be a panel of already
+// normalised bf16 rows with row stride lda, a multiple of 32, zero padded beyond d (the norm
+// kernel above writes it); W rows are read in place.
 //
 // Stage layout: W tile [256 rows][64 B] then A tile [256 rows][64 B]; the 16-byte chunk index is
 // XOR-swizzled with (row/4)%4, which makes the 16 rows x 4 chunks that one load instruction
 // writes (1 KB, lane-linear) and the 32 rows x 1 chunk that a fragment read touches both
 // bank-conflict free.
+//
+// Schedule of stage g (buffer g%3), with the barrier in the middle of the stage so that no LDS
+// read latency is ever exposed behind it:
+//   first half : MFMAs on the k-slice 0 fragments (already in registers), interleaved with the
+//                LDS reads of the k-slice 1 fragments of stage g;
+//   wait + barrier: stage g+1 has landed for everyone, and everyone holds all of stage g in
+//                registers, so buffer g%3 is free;
+//   second half: MFMAs on the k-slice 1 fragments, interleaved with the 8 loads of stage g+3 into
+//                buffer g%3 and the LDS reads of the k-slice 0 fragments of stage g+1.
+// The ring is fed unconditionally and runs on across vocabulary tiles (the next tile's first
+// stages load under the epilogue); past the last real stage it re-fetches the last tile, never
+// consumed, which keeps the count of loads in flight, and with it the s_waitcnt, constant.
 // ---------------------------------------------------------------------------------------
 constexpr int DK = 32;
+constexpr int NST = 3;
 constexpr int STAGE_BYTES = (BM + BN) * DK * 2;
 constexpr int LOADS_PER_STAGE = 8;   // per wavefront: 4 W segments + 4 A segments of 1 KB
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-template <int NST>
+#define LL_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   extern __shared__ __align__(16) unsigned char smem[];
-  EpiLds L;
-  L.listV = reinterpret_cast<float*>(smem + NST * STAGE_BYTES);
-  L.listI = reinterpret_cast<int*>(L.listV + p.k * BN);
-  L.queV = reinterpret_cast<float*>(L.listI + p.k * BN);
-  L.queI = reinterpret_cast<int*>(L.queV + QCAP * NTHREADS);
+  TopLists list = reinterpret_cast<uint2*>(smem + NST * STAGE_BYTES);
 
   const int logical = xcd_logical_block();
   if (logical >= p.row_blocks * p.splits) return;
@@ -476,23 +511,36 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   const int seg_koff = (((lane & 3) ^ ((lane >> 4) & 3))) * 8;   // element offset inside the K step
   const unsigned char* a_base = reinterpret_cast<const unsigned char*>(p.A + (int64_t)rb * BN * lda);
   const int a_last = p.rows - 1 - rb * BN;                       // last valid row of this block
+  unsigned a_row_off[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) a_row_off[s] = (unsigned)(min(seg_row + 16 * s, a_last) * lda + seg_koff) * 2u;
+
   int i_tile = tile0, i_kt = 0, i_buf = 0;                       // next stage to issue
-  auto issue = [&]() {
-    unsigned char* stage = smem + i_buf * STAGE_BYTES + (64 * wave) * (DK * 2);
-    const unsigned char* w_base = reinterpret_cast<const unsigned char*>(p.W + (int64_t)i_tile * BM * d);
-    const int w_last = V - 1 - i_tile * BM;
+  const unsigned char* w_base = nullptr;
+  unsigned w_k_off = 0, a_k_off = 0;
+  int w_last = 0;
+  auto issue_begin = [&]() {
+    const int t = i_tile < tile1 ? i_tile : tile1 - 1;
+    w_base = reinterpret_cast<const unsigned char*>(p.W + (int64_t)t * BM * d);
+    w_last = V - 1 - t * BM;
     int wk = i_kt * DK + seg_koff;
     wk = wk < d - 8 ? wk : d - 8;              // beyond d the A panel is zero: any finite W chunk will do
-    const int ak = i_kt * DK + seg_koff;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int wr = min(seg_row + 16 * s, w_last);
-      const int ar = min(seg_row + 16 * s, a_last);
-      const unsigned w_off = (unsigned)(wr * d + wk) * 2u;
-      const unsigned a_off = (unsigned)(ar * lda + ak) * 2u;
-      __builtin_amdgcn_global_load_lds((gptr_t)(w_base + w_off), (lptr_t)(stage + s * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(a_base + a_off), (lptr_t)(stage + BM * DK * 2 + s * 1024), 16, 0, 0);
+    w_k_off = (unsigned)wk * 2u;
+    a_k_off = (unsigned)(i_kt * DK) * 2u;
+  };
+  // one of the 8 loads of the stage: even n = W segment n/2, odd n = A segment n/2
+  auto issue_one = [&](int n) {
+    unsigned char* stage = smem + i_buf * STAGE_BYTES + (64 * wave) * (DK * 2);
+    const int s = n >> 1;
+    if ((n & 1) == 0) {
+      const unsigned off = (unsigned)(min(seg_row + 16 * s, w_last) * d) * 2u + w_k_off;
+      __builtin_amdgcn_global_load_lds((gptr_t)(w_base + off), (lptr_t)(stage + s * 1024), 16, 0, 0);
+    } else {
+      const unsigned off = a_row_off[s] + a_k_off;
+      __builtin_amdgcn_global_load_lds((gptr_t)(a_base + off), (lptr_t)(stage + BM * DK * 2 + s * 1024), 16, 0, 0);
     }
+  };
+  auto issue_end = [&]() {
     i_buf = i_buf + 1 == NST ? 0 : i_buf + 1;
     if (++i_kt == KT) {
       i_kt = 0;
@@ -504,23 +552,30 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   const int f_row = lane & 31;
   const int f_half = lane >> 5;
   const int f_swz = (f_row >> 2) & 3;
-  const int f_off0 = f_row * (DK * 2) + ((f_half ^ f_swz) * 16);         // kk = 0
-  const int f_off1 = f_row * (DK * 2) + (((2 + f_half) ^ f_swz) * 16);   // kk = 1
+  const int f_off0 = f_row * (DK * 2) + ((f_half ^ f_swz) * 16);         // k-slice 0
+  const int f_off1 = f_row * (DK * 2) + (((2 + f_half) ^ f_swz) * 16);   // k-slice 1
+  const int a_tile_off = BM * DK * 2 + (wave * 64) * (DK * 2);
 
   const int my_row = rb * BN + tid;
   RowState st;
   st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
-  epilogue_init(L, k, tid);
+  epilogue_init(list, k, tid);
 
-  int to_issue = (tile1 - tile0) * KT;      // stages not yet issued
-  int pending = 0;                          // stages issued and not yet consumed
+  // prologue: three stages in flight, the first one landed and its k-slice 0 fragments read
 #pragma unroll
-  for (int s = 0; s < NST - 1; ++s)
-    if (to_issue > 0) {
-      issue();
-      --to_issue;
-      ++pending;
-    }
+  for (int s = 0; s < NST; ++s) {
+    issue_begin();
+#pragma unroll
+    for (int n = 0; n < LOADS_PER_STAGE; ++n) issue_one(n);
+    issue_end();
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LOADS_PER_STAGE & 0xF) | ((2 * LOADS_PER_STAGE >> 4) << 14));   // vmcnt(16)
+  __syncthreads();
+  bf16x8 fa0[2], fw0[8], fa1[2], fw1[8];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) fa0[j] = *reinterpret_cast<const bf16x8*>(smem + a_tile_off + j * 32 * (DK * 2) + f_off0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) fw0[i] = *reinterpret_cast<const bf16x8*>(smem + i * 32 * (DK * 2) + f_off0);
 
   int buf = 0;
   for (int tile = tile0; tile < tile1; ++tile) {
@@ -533,75 +588,74 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     for (int kt = 0; kt < KT; ++kt) {
-      // The oldest pending stage has landed once at most the later ones' loads are outstanding.
-      if (NST >= 3 && pending >= 2) {
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (LOADS_PER_STAGE * (NST - 2)));   // vmcnt(8 * (NST-2)), NST <= 3
-      } else {
-        __builtin_amdgcn_s_waitcnt(0x0F70);                                  // vmcnt(0)
-      }
-      __syncthreads();   // everyone's part of this stage is visible; everyone is done with the previous one
-      --pending;
-      if (to_issue > 0) {                    // refill the buffer the previous stage used
-        issue();
-        --to_issue;
-        ++pending;
-      }
       const unsigned char* sW = smem + buf * STAGE_BYTES;
-      const unsigned char* sA = sW + BM * DK * 2 + (wave * 64) * (DK * 2);
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        const int off = kk == 0 ? f_off0 : f_off1;
-        bf16x8 fa[2], fw[8];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(sA + j * 32 * (DK * 2) + off);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) fw[i] = *reinterpret_cast<const bf16x8*>(sW + i * 32 * (DK * 2) + off);
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
-      }
-      // Pin the order: all 10 fragment reads of kk = 0 up front, the 10 of kk = 1 one by one
-      // under the first MFMAs, so that LDS latency hides behind matrix work.
-      __builtin_amdgcn_sched_group_barrier(0x100, 10, 0);
-#pragma unroll
-      for (int i = 0; i < 10; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 22, 0);
+      const unsigned char* sA = sW + a_tile_off;
       buf = buf + 1 == NST ? 0 : buf + 1;
+      const unsigned char* nW = smem + buf * STAGE_BYTES;
+      const unsigned char* nA = nW + a_tile_off;
+
+      // ---- first half: k-slice 0 MFMAs; k-slice 1 fragments of this stage come in underneath
+      LL_SCHED_FENCE();
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw0[i], fa0[0], acc[i][0], 0, 0, 0);
+        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw0[i], fa0[1], acc[i][1], 0, 0, 0);
+        if (i == 0) {
+          fa1[0] = *reinterpret_cast<const bf16x8*>(sA + f_off1);
+          fa1[1] = *reinterpret_cast<const bf16x8*>(sA + 32 * (DK * 2) + f_off1);
+        }
+        fw1[i] = *reinterpret_cast<const bf16x8*>(sW + i * 32 * (DK * 2) + f_off1);
+        LL_SCHED_FENCE();
+      }
+      // ---- stage g+1 landed (only stage g+2's loads may still be out); all my reads of stage g done
+      __builtin_amdgcn_s_waitcnt(0x0070 | LOADS_PER_STAGE);   // vmcnt(8) lgkmcnt(0)
+      __syncthreads();
+      // ---- second half: k-slice 1 MFMAs; refill this stage's buffer; next stage's k-slice 0 fragments
+      issue_begin();
+      LL_SCHED_FENCE();
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw1[i], fa1[0], acc[i][0], 0, 0, 0);
+        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw1[i], fa1[1], acc[i][1], 0, 0, 0);
+        issue_one(i);
+        if (i == 0) {
+          fa0[0] = *reinterpret_cast<const bf16x8*>(nA + f_off0);
+          fa0[1] = *reinterpret_cast<const bf16x8*>(nA + 32 * (DK * 2) + f_off0);
+        }
+        fw0[i] = *reinterpret_cast<const bf16x8*>(nW + i * 32 * (DK * 2) + f_off0);
+        LL_SCHED_FENCE();
+      }
+      issue_end();
     }
-    epilogue_tile(acc, st, L, tile * BM, V, k, tid);
+    epilogue_tile(acc, st, list, tile * BM, V, k, tid);
   }
-  epilogue_store(p, st, L, my_row, split, tid);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the ring before the LDS is given back
+  epilogue_store(p, st, list, my_row, split, tid);
 }
 
 // ---------------------------------------------------------------------------------------
 // a8: merge the splits of each row and finalise.  One thread per row.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void ll_merge_kernel(const float* __restrict__ stats, const float* __restrict__ topv,
-                                                       const int32_t* __restrict__ topi, int rows, int splits, int k, int V,
+__global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict__ stats, const uint2* __restrict__ top,
+                                                       int rows, int splits, int k, int V,
                                                        const int32_t* __restrict__ target, int32_t* __restrict__ out_ids,
                                                        float* __restrict__ out_p, float* __restrict__ out_logp,
                                                        float* __restrict__ out_entropy) {
   const int row = blockIdx.x * blockDim.x + threadIdx.x;
   if (row >= rows) return;
-  const float4* st = reinterpret_cast<const float4*>(stats) + (int64_t)row * splits;
+  const float4* st = stats + (int64_t)row * splits;
   float M = -INFINITY;
   for (int s = 0; s < splits; ++s) M = fmaxf(M, st[s].x);
-  float S = 0.f, U = 0.f, zt = -INFINITY;
+  float S = 0.f, T = 0.f, zt = -INFINITY;
   for (int s = 0; s < splits; ++s) {
     const float4 q = st[s];
-    const float dm = q.x - M;
-    const float sc = __builtin_amdgcn_exp2f(dm * LOG2E);
+    const float sc = __builtin_amdgcn_exp2f((q.x - M) * LOG2E);
     S += sc * q.y;
-    U += sc * fmaf(dm, q.y, q.z);
+    T += sc * q.z;
     zt = fmaxf(zt, q.w);
   }
   const float logS = logf(S);
-  out_entropy[row] = logS - U / S;
+  out_entropy[row] = (M - T / S) + logS;
   if (target != nullptr) {
     const int t = target[row];
     out_logp[row] = (t >= 0 && t < V) ? (zt - M) - logS : __builtin_nanf("");
@@ -610,16 +664,16 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float* __restrict__
   int head[MAX_SPLITS];
 #pragma unroll
   for (int s = 0; s < MAX_SPLITS; ++s) head[s] = 0;
-  const float* tv = topv + (int64_t)row * splits * k;
-  const int32_t* ti = topi + (int64_t)row * splits * k;
+  const uint2* tl = top + (int64_t)row * splits * k;
   for (int j = 0; j < k; ++j) {
     float bz = -INFINITY;
     int bi = INT_MAX, bs = 0;
 #pragma unroll
     for (int s = 0; s < MAX_SPLITS; ++s) {
       if (s < splits && head[s] < k) {
-        const float z = tv[s * k + head[s]];
-        const int id = ti[s * k + head[s]];
+        const uint2 e = tl[s * k + head[s]];
+        const float z = __uint_as_float(e.x);
+        const int id = (int)e.y;
         if (z > bz || (z == bz && id < bi)) {
           bz = z;
           bi = id;
@@ -639,7 +693,7 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float* __restrict__
 // host side
 // ---------------------------------------------------------------------------------------
 struct Plan {
-  size_t off_inv_rms, off_stats, off_topv, off_topi, off_panel, total;
+  size_t off_inv_rms, off_stats, off_top, off_panel, total;
   int64_t lda;
 };
 
@@ -657,11 +711,9 @@ Plan make_plan(const ll_shape* s, int k) {
   off = align_up(off + (size_t)s->N * sizeof(float), 256);
   const size_t rows = (size_t)(s->N < CHUNK_ROWS ? s->N : CHUNK_ROWS);
   p.off_stats = off;
-  off = align_up(off + rows * MAX_SPLITS * 4 * sizeof(float), 256);
-  p.off_topv = off;
-  off = align_up(off + rows * MAX_SPLITS * (size_t)k * sizeof(float), 256);
-  p.off_topi = off;
-  off = align_up(off + rows * MAX_SPLITS * (size_t)k * sizeof(int32_t), 256);
+  off = align_up(off + rows * MAX_SPLITS * sizeof(float4), 256);
+  p.off_top = off;
+  off = align_up(off + rows * MAX_SPLITS * (size_t)k * sizeof(uint2), 256);
   p.lda = (s->d + DK - 1) / DK * DK;
   p.off_panel = off;
   off = align_up(off + rows * (size_t)p.lda * sizeof(uint16_t), 256);
@@ -669,12 +721,10 @@ Plan make_plan(const ll_shape* s, int k) {
   return p;
 }
 
-constexpr size_t LDS_MAX = 160 * 1024;
-size_t epi_lds_bytes(int k) { return (size_t)k * BN * 8 + (size_t)QCAP * NTHREADS * 8; }
-size_t gemm_lds_bytes(int k) { return (size_t)(BM + BN) * BK * 2 + epi_lds_bytes(k); }
+size_t list_lds_bytes(int k) { return (size_t)k * BN * sizeof(uint2); }
 
-// 0: automatic; 1: register-staged kernel with the norm fused into the A-tile load; 2: DMA kernel
-// fed from a normalised panel.
+// 0: automatic; 1: register-staged kernel with the norm fused into the A-tile load; 2: direct-to-LDS
+// kernel fed from a normalised panel.
 int g_gemm_path = 0;
 
 int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
@@ -696,21 +746,21 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
 
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   float* inv_rms = reinterpret_cast<float*>(ws + plan.off_inv_rms);
-  float* stats = reinterpret_cast<float*>(ws + plan.off_stats);
-  float* topv = reinterpret_cast<float*>(ws + plan.off_topv);
-  int32_t* topi = reinterpret_cast<int32_t*>(ws + plan.off_topi);
+  float4* stats = reinterpret_cast<float4*>(ws + plan.off_stats);
+  uint2* top = reinterpret_cast<uint2*>(ws + plan.off_top);
   uint16_t* panel = reinterpret_cast<uint16_t*>(ws + plan.off_panel);
 
   const int64_t N = shape->N;
   const int d = shape->d, V = shape->V;
   const bool has_gamma = gamma != nullptr;
-  const bool dma = g_gemm_path != 1;
-  const int nst = (size_t)3 * STAGE_BYTES + epi_lds_bytes(k) <= LDS_MAX ? 3 : 2;
-  const size_t lds = dma ? (size_t)nst * STAGE_BYTES + epi_lds_bytes(k) : gemm_lds_bytes(k);
-  void (*kern)(const GemmArgs) = dma ? (nst == 3 ? ll_lens_gemm_dma_kernel<3> : ll_lens_gemm_dma_kernel<2>)
-                                     : (has_gamma ? ll_lens_gemm_kernel<true> : ll_lens_gemm_kernel<false>);
+  // The direct-to-LDS kernel addresses rows with 32-bit byte offsets from a per-tile base.
+  const bool dma_ok = (int64_t)BM * d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * plan.lda * 2 < (int64_t)1 << 31;
+  const bool dma = g_gemm_path != 1 && dma_ok;
+  const size_t lds = (dma ? (size_t)NST * STAGE_BYTES : (size_t)(BM + BN) * BK * 2) + list_lds_bytes(k);
+  void (*kern)(const GemmArgs) =
+      dma ? ll_lens_gemm_dma_kernel : (has_gamma ? ll_lens_gemm_kernel<true> : ll_lens_gemm_kernel<false>);
   LL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  // The DMA kernel reads hidden in place when the rows need neither scaling nor padding.
+  // The direct-to-LDS kernel reads hidden in place when the rows need neither scaling nor padding.
   const bool need_panel = dma && (has_gamma || plan.lda != d);
 
   // Timing (ll_project_timed only): events are recorded in-stream around every kernel and read
@@ -768,8 +818,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     a.W = static_cast<const uint16_t*>(W_U);
     a.target = target_ids ? target_ids + r0 : nullptr;
     a.stats = stats;
-    a.topv = topv;
-    a.topi = topi;
+    a.top = top;
     a.rows = rows;
     a.d = d;
     a.V = V;
@@ -782,8 +831,8 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHREADS), lds, stream, a);
     LL_CHECK_F(hipGetLastError());
     LL_CHECK_F(mark());
-    hipLaunchKernelGGL(ll_merge_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, stats, topv, topi, rows, splits, k, V,
-                       a.target, out_topk_ids + r0 * k, out_topk_p + r0 * k,
+    hipLaunchKernelGGL(ll_merge_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, (const float4*)stats, (const uint2*)top,
+                       rows, splits, k, V, a.target, out_topk_ids + r0 * k, out_topk_p + r0 * k,
                        out_target_logp ? out_target_logp + r0 : nullptr, out_entropy + r0);
     LL_CHECK_F(hipGetLastError());
     LL_CHECK_F(mark());
