@@ -133,20 +133,42 @@ struct GemmArgs {
 // Epilogue shared by both GEMM kernels.  State of one lens row, private to the lane that owns it.
 // With m the running maximum: S = sum exp(z - m), T = sum exp(z - m) z.  Then
 // logsumexp = m + log S and entropy = m + log S - T / S.
+// The row's best KR logits (KR >= k) sit in registers, sorted: descending logit, and among equal
+// logits ascending id.  A workgroup meets its vocabulary ids in increasing order, so a new
+// candidate never outranks an equal logit already listed and a strict comparison is exact.
 // ---------------------------------------------------------------------------------------
+template <int KR>
 struct RowState {
   float m = -INFINITY;
   float s = 0.f;
   float t = 0.f;
   float z_tgt = -INFINITY;  // logit of the target id, once its tile has passed
-  float tau = -INFINITY;    // current k-th best logit (list tail)
-  int tau_id = INT_MAX;
   int tgt = -1;             // target id of the row (-1: none)
+  float lv[KR];             // top logits
+  int li[KR];               // their ids
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int j = 0; j < KR; ++j) {
+      lv[j] = -INFINITY;
+      li[j] = INT_MAX;
+    }
+  }
+  __device__ __forceinline__ float tau() const { return lv[KR - 1]; }
+  // Branch-free sorted insert: slot j takes its upper neighbour if the candidate goes above that
+  // neighbour, the candidate if it goes exactly here, and keeps its entry otherwise.
+  __device__ __forceinline__ void insert(float z, int id) {
+    bool above = z > lv[KR - 1];              // candidate ranks above the entry of slot j
+#pragma unroll
+    for (int j = KR - 1; j >= 1; --j) {
+      const bool above_up = z > lv[j - 1];
+      lv[j] = above_up ? lv[j - 1] : (above ? z : lv[j]);
+      li[j] = above_up ? li[j - 1] : (above ? id : li[j]);
+      above = above_up;
+    }
+    lv[0] = above ? z : lv[0];
+    li[0] = above ? id : li[0];
+  }
 };
-
-// Sorted top-k lists of the workgroup's 256 rows in LDS: entry j of row r at [j][r] as
-// (logit bits, id); descending logit, ascending id among equal logits.
-typedef uint2* TopLists;
 
 // Reads one accumulator element where it lives (an AGPR) at the point of use, so that the
 // register allocator does not copy the whole 256-register tile into VGPRs ahead of the epilogue.
@@ -154,46 +176,6 @@ __device__ __forceinline__ float acc_read(float a) {
   float v;
   asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
   return v;
-}
-
-__device__ __forceinline__ void epilogue_init(TopLists list, int k, int tid) {
-  for (int j = 0; j < k; ++j) list[j * BN + tid] = make_uint2(__float_as_uint(-INFINITY), (unsigned)INT_MAX);
-}
-
-// true if list entry e ranks above the candidate (z, id)
-__device__ __forceinline__ bool ranks_above(const uint2 e, float z, int id) {
-  const float ev = __uint_as_float(e.x);
-  return ev > z || (ev == z && (int)e.y < id);
-}
-
-// Inserts (z, id), which is known to rank above the current tail, into the lane's sorted list.
-// Walks up from the tail four entries at a time so that the LDS round trips overlap.
-__device__ __forceinline__ void topk_insert(TopLists list, int k, int tid, float z, int id, RowState& st) {
-  const uint2 cand = make_uint2(__float_as_uint(z), (unsigned)id);
-  uint2* col = list + tid;
-  int j = k - 1;                 // slot the candidate would take if nothing above it moves
-  uint2 new_tail = cand;
-  bool first = true;
-  while (j > 0) {
-    const uint2 e1 = col[(j - 1) * BN];
-    const uint2 e2 = col[(j >= 2 ? j - 2 : 0) * BN];
-    const uint2 e3 = col[(j >= 3 ? j - 3 : 0) * BN];
-    const uint2 e4 = col[(j >= 4 ? j - 4 : 0) * BN];
-    if (ranks_above(e1, z, id)) break;
-    if (first) new_tail = e1;    // the old second-to-last entry becomes the tail
-    first = false;
-    col[j * BN] = e1;
-    if (j < 2 || ranks_above(e2, z, id)) { j -= 1; break; }
-    col[(j - 1) * BN] = e2;
-    if (j < 3 || ranks_above(e3, z, id)) { j -= 2; break; }
-    col[(j - 2) * BN] = e3;
-    if (j < 4 || ranks_above(e4, z, id)) { j -= 3; break; }
-    col[(j - 3) * BN] = e4;
-    j -= 4;
-  }
-  col[j * BN] = cand;
-  st.tau = __uint_as_float(new_tail.x);
-  st.tau_id = (int)new_tail.y;
 }
 
 // x[o] for a per-lane o in [0, 32): registers cannot be indexed by a lane-varying position, so
@@ -225,9 +207,8 @@ __device__ __forceinline__ float select32(const float (&x)[32], int o) {
 }
 
 // Processes vocabulary entries [v0 + 32 I, v0 + 32 I + 32) of the finished tile for the lane's row.
-template <int I>
-__device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowState& st, TopLists list, int v0, int V,
-                                               int k, bool partial, int tid) {
+template <int I, int KR>
+__device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowState<KR>& st, int v0, int V, bool partial) {
   // x[o]: logit of vocabulary entry v0 + 32 I + o for this lane's row.  The swap hands the lower
   // lane half the row tile j = 0 and the upper half j = 1, so that lane l owns row 64 w + l.
   float x[32];
@@ -274,46 +255,47 @@ __device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowSta
   st.s += (s4[0] + s4[1]) + (s4[2] + s4[3]);
   st.t += (t4[0] + t4[1]) + (t4[2] + t4[3]);
 
-  // a6: streaming top-k.  Only when some lane of the wavefront has a logit that reaches its
-  // current k-th best: mark the candidates against the threshold, then insert them one by one
-  // (the exact comparison against the moving tail happens at insertion).
-  if (__builtin_amdgcn_ballot_w64(gmax >= st.tau) != 0) {
+  // a6: streaming top-k.  Only when some lane of the wavefront has a logit above its current
+  // KR-th best: mark the candidates against that threshold, then insert them in id order.
+  if (__builtin_amdgcn_ballot_w64(gmax > st.tau()) != 0) {
+    const float tau0 = st.tau();
     unsigned mask = 0;
 #pragma unroll
-    for (int o = 0; o < 32; ++o) mask |= (x[o] >= st.tau ? 1u : 0u) << o;
+    for (int o = 0; o < 32; ++o) mask |= (x[o] > tau0 ? 1u : 0u) << o;
+    if (partial) mask &= (g0 + 32 <= V) ? 0xffffffffu : (g0 >= V ? 0u : (1u << (V - g0)) - 1u);
     while (mask != 0) {
       const int o = __builtin_ctz(mask);
       mask &= mask - 1;
-      const float z = select32(x, o);
-      const int id = g0 + o;
-      if (id < V && (z > st.tau || (z == st.tau && id < st.tau_id))) topk_insert(list, k, tid, z, id, st);
+      st.insert(select32(x, o), g0 + o);
     }
   }
 }
 
-__device__ __forceinline__ void epilogue_tile(const f32x16 (&acc)[8][2], RowState& st, TopLists list, int v0, int V,
-                                              int k, int tid) {
+template <int KR>
+__device__ __forceinline__ void epilogue_tile(const f32x16 (&acc)[8][2], RowState<KR>& st, int v0, int V) {
   const bool partial = v0 + BM > V;
   // The accumulators are read below through inline asm, which the compiler's MFMA hazard
   // bookkeeping does not see: let the last MFMA of the tile drain first.
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-  epilogue_group<0>(acc, st, list, v0, V, k, partial, tid);
-  epilogue_group<1>(acc, st, list, v0, V, k, partial, tid);
-  epilogue_group<2>(acc, st, list, v0, V, k, partial, tid);
-  epilogue_group<3>(acc, st, list, v0, V, k, partial, tid);
-  epilogue_group<4>(acc, st, list, v0, V, k, partial, tid);
-  epilogue_group<5>(acc, st, list, v0, V, k, partial, tid);
-  epilogue_group<6>(acc, st, list, v0, V, k, partial, tid);
-  epilogue_group<7>(acc, st, list, v0, V, k, partial, tid);
+  epilogue_group<0>(acc, st, v0, V, partial);
+  epilogue_group<1>(acc, st, v0, V, partial);
+  epilogue_group<2>(acc, st, v0, V, partial);
+  epilogue_group<3>(acc, st, v0, V, partial);
+  epilogue_group<4>(acc, st, v0, V, partial);
+  epilogue_group<5>(acc, st, v0, V, partial);
+  epilogue_group<6>(acc, st, v0, V, partial);
+  epilogue_group<7>(acc, st, v0, V, partial);
 }
 
-// Per-(row, split) partial results: (m, S, T, z_target) and the sorted top-k list.
-__device__ __forceinline__ void epilogue_store(const GemmArgs& p, const RowState& st, TopLists list, int my_row, int split,
-                                               int tid) {
+// Per-(row, split) partial results: (m, S, T, z_target) and the k best (logit bits, id) pairs.
+template <int KR>
+__device__ __forceinline__ void epilogue_store(const GemmArgs& p, const RowState<KR>& st, int my_row, int split) {
   if (my_row >= p.rows) return;
   const int64_t o = (int64_t)my_row * p.splits + split;
   p.stats[o] = make_float4(st.m, st.s, st.t, st.z_tgt);
-  for (int j = 0; j < p.k; ++j) p.top[o * p.k + j] = list[j * BN + tid];
+#pragma unroll
+  for (int j = 0; j < KR; ++j)
+    if (j < p.k) p.top[o * p.k + j] = make_uint2(__float_as_uint(st.lv[j]), (unsigned)st.li[j]);
 }
 
 // Workgroup ids are dealt round-robin over the 8 XCDs; remap so that one XCD (one L2) gets a
@@ -332,13 +314,13 @@ __device__ __forceinline__ int xcd_logical_block() {
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ int lds_off(int row, int chunk) { return (row * 8 + (chunk ^ ((row >> 1) & 7))) * 16; }
 
-template <bool FUSED_NORM>
+template <int KR>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void ll_lens_gemm_kernel(const GemmArgs p) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* sW = smem;
   unsigned char* sA = smem + BM * BK * 2;
-  TopLists list = reinterpret_cast<uint2*>(smem + (BM + BN) * BK * 2);
+  const bool FUSED_NORM = p.inv_rms != nullptr;
 
   const int logical = xcd_logical_block();
   if (logical >= p.row_blocks * p.splits) return;
@@ -350,7 +332,7 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int d = p.d, V = p.V, k = p.k;
+  const int d = p.d, V = p.V;
   const int64_t lda = p.lda;
 
   // --- global -> LDS staging map: thread handles physical chunk (tid % 8) of rows tid/8 + 32 i.
@@ -374,9 +356,9 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
 
   // --- epilogue state: this lane owns lens row (rb*BN + tid).
   const int my_row = rb * BN + tid;
-  RowState st;
+  RowState<KR> st;
+  st.init();
   st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
-  epilogue_init(list, k, tid);
 
   const int KT = (d + BK - 1) / BK;
 
@@ -447,48 +429,52 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
       }
     }
-    epilogue_tile(acc, st, list, v0, V, k, tid);
+    epilogue_tile(acc, st, v0, V);
   }
-  epilogue_store(p, st, list, my_row, split, tid);
+  epilogue_store(p, st, my_row, split);
 }
 
 // ---------------------------------------------------------------------------------------
 // Direct-to-LDS kernel: both operands go from global memory straight into LDS (global_load_lds,
-// 16 bytes per lane) through a ring of 3 stages of K = 32.  A must be a panel of already
-// normalised bf16 rows with row stride lda, a multiple of 32, zero padded beyond d (the norm
-// kernel above writes it); W rows are read in place.
+// 16 bytes per lane) through two stage buffers of K = 64, so that every load instruction takes
+// whole 128-byte lines (8 rows x 128 B).  A must be a panel of already normalised bf16 rows with
+// row stride lda, a multiple of 64, zero padded beyond d (the norm kernel above writes it); W rows
+// are read in place.
 //
-// Stage layout: W tile [256 rows][64 B] then A tile [256 rows][64 B]; the 16-byte chunk index is
-// XOR-swizzled with (row/4)%4, which makes the 16 rows x 4 chunks that one load instruction
+// Stage layout: W tile [256 rows][128 B] then A tile [256 rows][128 B]; the 16-byte chunk index
+// is XOR-swizzled with (row/2)%8, which makes the 8 rows x 8 chunks that one load instruction
 // writes (1 KB, lane-linear) and the 32 rows x 1 chunk that a fragment read touches both
 // bank-conflict free.
 //
-// Schedule of stage g (buffer g%3), with the barrier in the middle of the stage so that no LDS
-// read latency is ever exposed behind it:
-//   first half : MFMAs on the k-slice 0 fragments (already in registers), interleaved with the
-//                LDS reads of the k-slice 1 fragments of stage g;
-//   wait + barrier: stage g+1 has landed for everyone, and everyone holds all of stage g in
-//                registers, so buffer g%3 is free;
-//   second half: MFMAs on the k-slice 1 fragments, interleaved with the 8 loads of stage g+3 into
-//                buffer g%3 and the LDS reads of the k-slice 0 fragments of stage g+1.
+// Schedule of stage g (buffer g%2), four k-slices of 16; fragments alternate between two
+// register sets, and the barrier sits before the last slice so that no LDS latency hides behind it:
+//   slices 0..2: MFMAs on the slice's fragments (already in registers), interleaved with the LDS
+//                reads of the next slice's fragments;
+//   wait + barrier: stage g+1 has landed for everyone, and everyone holds the last slice of
+//                stage g in registers, so buffer g%2 is free;
+//   slice 3    : its MFMAs, interleaved with the 16 loads of stage g+2 into buffer g%2 and the LDS
+//                reads of slice 0 of stage g+1.
 // The ring is fed unconditionally and runs on across vocabulary tiles (the next tile's first
-// stages load under the epilogue); past the last real stage it re-fetches the last tile, never
+// stage loads under the epilogue); past the last real stage it re-fetches the last tile, never
 // consumed, which keeps the count of loads in flight, and with it the s_waitcnt, constant.
 // ---------------------------------------------------------------------------------------
-constexpr int DK = 32;
-constexpr int NST = 3;
+constexpr int DK = 64;
+constexpr int NST = 2;
 constexpr int STAGE_BYTES = (BM + BN) * DK * 2;
-constexpr int LOADS_PER_STAGE = 8;   // per wavefront: 4 W segments + 4 A segments of 1 KB
+constexpr int LOADS_PER_STAGE = 16;   // per wavefront: 8 W segments + 8 A segments of 1 KB
+// s_waitcnt immediate (gfx9 layout): vmcnt in bits 3:0 and 15:14, expcnt 6:4 (7 = no wait), lgkmcnt 11:8.
+constexpr int waitcnt_imm(int vmcnt, int lgkmcnt) { return (vmcnt & 0xF) | ((vmcnt >> 4) << 14) | 0x70 | (lgkmcnt << 8); }
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 #define LL_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define LL_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
+template <int KR>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   extern __shared__ __align__(16) unsigned char smem[];
-  TopLists list = reinterpret_cast<uint2*>(smem + NST * STAGE_BYTES);
 
   const int logical = xcd_logical_block();
   if (logical >= p.row_blocks * p.splits) return;
@@ -500,68 +486,67 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int d = p.d, V = p.V, k = p.k;
+  const int d = p.d, V = p.V;
   const int lda = (int)p.lda;
   const int KT = lda / DK;
 
-  // --- DMA map.  One load instruction fills 16 rows x 64 B; lane l lands at row l/4, physical
-  // chunk l%4, so it fetches logical chunk (l%4) ^ ((l/16)%4).  Wavefront w fills rows
-  // [64w, 64w+64) of both tiles.  Addresses are a wave-uniform base plus a 32-bit byte offset.
-  const int seg_row = 64 * wave + (lane >> 2);                   // + 16 s
-  const int seg_koff = (((lane & 3) ^ ((lane >> 4) & 3))) * 8;   // element offset inside the K step
+  // --- DMA map.  One load instruction fills 8 rows x 128 B; lane l lands at row l/8, physical
+  // chunk l%8.  Wavefront w fills rows [64w, 64w+64) of both tiles in 8 segments; segment s holds
+  // rows 64w + 8s + l/8, whose swizzle is (l/16 + 4s) % 8, so the lane fetches logical chunk
+  // (l%8) ^ (l/16) ^ 4(s%2).  Addresses are a wave-uniform base plus a 32-bit byte offset.
+  const int seg_row = 64 * wave + (lane >> 3);                        // + 8 s
+  const int seg_koff0 = ((lane & 7) ^ (lane >> 4)) * 8;               // element offset, even segments
+  const int seg_koff1 = seg_koff0 ^ 32;                               // odd segments
   const unsigned char* a_base = reinterpret_cast<const unsigned char*>(p.A + (int64_t)rb * BN * lda);
-  const int a_last = p.rows - 1 - rb * BN;                       // last valid row of this block
-  unsigned a_row_off[4];
-#pragma unroll
-  for (int s = 0; s < 4; ++s) a_row_off[s] = (unsigned)(min(seg_row + 16 * s, a_last) * lda + seg_koff) * 2u;
+  const int a_last = p.rows - 1 - rb * BN;                            // last valid row of this block
 
-  int i_tile = tile0, i_kt = 0, i_buf = 0;                       // next stage to issue
+  int i_tile = tile0, i_kt = 0, i_buf = 0;                            // next stage to issue
   const unsigned char* w_base = nullptr;
-  unsigned w_k_off = 0, a_k_off = 0;
-  int w_last = 0;
+  int w_last = 0, i_k0 = 0;
   auto issue_begin = [&]() {
     const int t = i_tile < tile1 ? i_tile : tile1 - 1;
     w_base = reinterpret_cast<const unsigned char*>(p.W + (int64_t)t * BM * d);
     w_last = V - 1 - t * BM;
-    int wk = i_kt * DK + seg_koff;
-    wk = wk < d - 8 ? wk : d - 8;              // beyond d the A panel is zero: any finite W chunk will do
-    w_k_off = (unsigned)wk * 2u;
-    a_k_off = (unsigned)(i_kt * DK) * 2u;
+    i_k0 = i_kt * DK;
   };
-  // one of the 8 loads of the stage: even n = W segment n/2, odd n = A segment n/2
+  // one of the 16 loads of the stage: even n = W segment n/2, odd n = A segment n/2
   auto issue_one = [&](int n) {
     unsigned char* stage = smem + i_buf * STAGE_BYTES + (64 * wave) * (DK * 2);
     const int s = n >> 1;
+    const int ko = i_k0 + ((s & 1) ? seg_koff1 : seg_koff0);
     if ((n & 1) == 0) {
-      const unsigned off = (unsigned)(min(seg_row + 16 * s, w_last) * d) * 2u + w_k_off;
+      const int wk = ko < d - 8 ? ko : d - 8;   // beyond d the A panel is zero: any finite W chunk will do
+      const unsigned off = (unsigned)(min(seg_row + 8 * s, w_last) * d + wk) * 2u;
       __builtin_amdgcn_global_load_lds((gptr_t)(w_base + off), (lptr_t)(stage + s * 1024), 16, 0, 0);
     } else {
-      const unsigned off = a_row_off[s] + a_k_off;
+      const unsigned off = (unsigned)(min(seg_row + 8 * s, a_last) * lda + ko) * 2u;
       __builtin_amdgcn_global_load_lds((gptr_t)(a_base + off), (lptr_t)(stage + BM * DK * 2 + s * 1024), 16, 0, 0);
     }
   };
   auto issue_end = [&]() {
-    i_buf = i_buf + 1 == NST ? 0 : i_buf + 1;
+    i_buf ^= 1;
     if (++i_kt == KT) {
       i_kt = 0;
       ++i_tile;
     }
   };
 
-  // --- MFMA fragment map: lane reads row (lane % 32) of each 32-row group, K chunk 2*kk + lane/32.
+  // --- MFMA fragment map: lane reads row (lane % 32) of each 32-row group; k-slice s is the
+  // logical 16-byte chunk 2s + lane/32 of the row.
   const int f_row = lane & 31;
   const int f_half = lane >> 5;
-  const int f_swz = (f_row >> 2) & 3;
-  const int f_off0 = f_row * (DK * 2) + ((f_half ^ f_swz) * 16);         // k-slice 0
-  const int f_off1 = f_row * (DK * 2) + (((2 + f_half) ^ f_swz) * 16);   // k-slice 1
+  const int f_swz = (f_row >> 1) & 7;
+  int f_off[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) f_off[s] = f_row * (DK * 2) + (((2 * s + f_half) ^ f_swz) * 16);
   const int a_tile_off = BM * DK * 2 + (wave * 64) * (DK * 2);
 
   const int my_row = rb * BN + tid;
-  RowState st;
+  RowState<KR> st;
+  st.init();
   st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
-  epilogue_init(list, k, tid);
 
-  // prologue: three stages in flight, the first one landed and its k-slice 0 fragments read
+  // prologue: both buffers in flight, the first one landed and its slice-0 fragments read
 #pragma unroll
   for (int s = 0; s < NST; ++s) {
     issue_begin();
@@ -569,13 +554,33 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
     for (int n = 0; n < LOADS_PER_STAGE; ++n) issue_one(n);
     issue_end();
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LOADS_PER_STAGE & 0xF) | ((2 * LOADS_PER_STAGE >> 4) << 14));   // vmcnt(16)
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(LOADS_PER_STAGE, 15));   // stage 0 landed
   __syncthreads();
   bf16x8 fa0[2], fw0[8], fa1[2], fw1[8];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) fa0[j] = *reinterpret_cast<const bf16x8*>(smem + a_tile_off + j * 32 * (DK * 2) + f_off0);
+  for (int j = 0; j < 2; ++j) fa0[j] = *reinterpret_cast<const bf16x8*>(smem + a_tile_off + j * 32 * (DK * 2) + f_off[0]);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) fw0[i] = *reinterpret_cast<const bf16x8*>(smem + i * 32 * (DK * 2) + f_off0);
+  for (int i = 0; i < 8; ++i) fw0[i] = *reinterpret_cast<const bf16x8*>(smem + i * 32 * (DK * 2) + f_off[0]);
+
+  // MFMAs of one k-slice from fragment set (fw, fa), with the LDS reads of another slice into
+  // (nw, na) from tiles (tW, tA) slipped in under the first four MFMA pairs, so that the last
+  // read has half a slice to land before the next slice needs it.
+#define LL_SLICE(fw, fa, nw, na, tW, tA, off, EXTRA)                                                \
+  LL_SCHED_FENCE();                                                                                 \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                   \
+    acc[i][0] = LL_MFMA(fw[i], fa[0], acc[i][0]);                                                   \
+    acc[i][1] = LL_MFMA(fw[i], fa[1], acc[i][1]);                                                   \
+    EXTRA;                                                                                          \
+    if (i == 0) {                                                                                   \
+      na[0] = *reinterpret_cast<const bf16x8*>(tA + (off));                                         \
+      na[1] = *reinterpret_cast<const bf16x8*>(tA + 32 * (DK * 2) + (off));                         \
+    }                                                                                               \
+    if (i < 4) {                                                                                    \
+      nw[2 * i] = *reinterpret_cast<const bf16x8*>(tW + (2 * i) * 32 * (DK * 2) + (off));           \
+      nw[2 * i + 1] = *reinterpret_cast<const bf16x8*>(tW + (2 * i + 1) * 32 * (DK * 2) + (off));   \
+    }                                                                                               \
+    LL_SCHED_FENCE();                                                                               \
+  }
 
   int buf = 0;
   for (int tile = tile0; tile < tile1; ++tile) {
@@ -590,47 +595,25 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
     for (int kt = 0; kt < KT; ++kt) {
       const unsigned char* sW = smem + buf * STAGE_BYTES;
       const unsigned char* sA = sW + a_tile_off;
-      buf = buf + 1 == NST ? 0 : buf + 1;
+      buf ^= 1;
       const unsigned char* nW = smem + buf * STAGE_BYTES;
       const unsigned char* nA = nW + a_tile_off;
 
-      // ---- first half: k-slice 0 MFMAs; k-slice 1 fragments of this stage come in underneath
-      LL_SCHED_FENCE();
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw0[i], fa0[0], acc[i][0], 0, 0, 0);
-        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw0[i], fa0[1], acc[i][1], 0, 0, 0);
-        if (i == 0) {
-          fa1[0] = *reinterpret_cast<const bf16x8*>(sA + f_off1);
-          fa1[1] = *reinterpret_cast<const bf16x8*>(sA + 32 * (DK * 2) + f_off1);
-        }
-        fw1[i] = *reinterpret_cast<const bf16x8*>(sW + i * 32 * (DK * 2) + f_off1);
-        LL_SCHED_FENCE();
-      }
-      // ---- stage g+1 landed (only stage g+2's loads may still be out); all my reads of stage g done
-      __builtin_amdgcn_s_waitcnt(0x0070 | LOADS_PER_STAGE);   // vmcnt(8) lgkmcnt(0)
+      LL_SLICE(fw0, fa0, fw1, fa1, sW, sA, f_off[1], (void)0)
+      LL_SLICE(fw1, fa1, fw0, fa0, sW, sA, f_off[2], (void)0)
+      LL_SLICE(fw0, fa0, fw1, fa1, sW, sA, f_off[3], (void)0)
+      // stage g+1 landed (its loads are the only ones out); all my reads of stage g done
+      __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
       __syncthreads();
-      // ---- second half: k-slice 1 MFMAs; refill this stage's buffer; next stage's k-slice 0 fragments
       issue_begin();
-      LL_SCHED_FENCE();
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw1[i], fa1[0], acc[i][0], 0, 0, 0);
-        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw1[i], fa1[1], acc[i][1], 0, 0, 0);
-        issue_one(i);
-        if (i == 0) {
-          fa0[0] = *reinterpret_cast<const bf16x8*>(nA + f_off0);
-          fa0[1] = *reinterpret_cast<const bf16x8*>(nA + 32 * (DK * 2) + f_off0);
-        }
-        fw0[i] = *reinterpret_cast<const bf16x8*>(nW + i * 32 * (DK * 2) + f_off0);
-        LL_SCHED_FENCE();
-      }
+      LL_SLICE(fw1, fa1, fw0, fa0, nW, nA, f_off[0], issue_one(2 * i); issue_one(2 * i + 1))
       issue_end();
     }
-    epilogue_tile(acc, st, list, tile * BM, V, k, tid);
+    epilogue_tile(acc, st, tile * BM, V);
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the ring before the LDS is given back
-  epilogue_store(p, st, list, my_row, split, tid);
+#undef LL_SLICE
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));   // drain the ring before the LDS is given back
+  epilogue_store(p, st, my_row, split);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -721,8 +704,6 @@ Plan make_plan(const ll_shape* s, int k) {
   return p;
 }
 
-size_t list_lds_bytes(int k) { return (size_t)k * BN * sizeof(uint2); }
-
 // 0: automatic; 1: register-staged kernel with the norm fused into the A-tile load; 2: direct-to-LDS
 // kernel fed from a normalised panel.
 int g_gemm_path = 0;
@@ -756,9 +737,17 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   // The direct-to-LDS kernel addresses rows with 32-bit byte offsets from a per-tile base.
   const bool dma_ok = (int64_t)BM * d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * plan.lda * 2 < (int64_t)1 << 31;
   const bool dma = g_gemm_path != 1 && dma_ok;
-  const size_t lds = (dma ? (size_t)NST * STAGE_BYTES : (size_t)(BM + BN) * BK * 2) + list_lds_bytes(k);
-  void (*kern)(const GemmArgs) =
-      dma ? ll_lens_gemm_dma_kernel : (has_gamma ? ll_lens_gemm_kernel<true> : ll_lens_gemm_kernel<false>);
+  const size_t lds = dma ? (size_t)NST * STAGE_BYTES : (size_t)(BM + BN) * BK * 2;
+  // The top-k lists live in registers: the kernels are built for a few list lengths KR >= k.
+  void (*kern)(const GemmArgs);
+  if (k <= 4)
+    kern = dma ? ll_lens_gemm_dma_kernel<4> : ll_lens_gemm_kernel<4>;
+  else if (k <= 12)
+    kern = dma ? ll_lens_gemm_dma_kernel<12> : ll_lens_gemm_kernel<12>;
+  else if (k <= 20)
+    kern = dma ? ll_lens_gemm_dma_kernel<20> : ll_lens_gemm_kernel<20>;
+  else
+    kern = dma ? ll_lens_gemm_dma_kernel<32> : ll_lens_gemm_kernel<32>;
   LL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   // The direct-to-LDS kernel reads hidden in place when the rows need neither scaling nor padding.
   const bool need_panel = dma && (has_gamma || plan.lda != d);
