@@ -436,32 +436,39 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
 
 // ---------------------------------------------------------------------------------------
 // Direct-to-LDS kernel: both operands go from global memory straight into LDS (global_load_lds,
-// 16 bytes per lane) through two stage buffers of K = 64, so that every load instruction takes
-// whole 128-byte lines (8 rows x 128 B).  A must be a panel of already normalised bf16 rows with
-// row stride lda, a multiple of 64, zero padded beyond d (the norm kernel above writes it); W rows
-// are read in place.
+// 16 bytes per lane) in stages of K = 64, so that every load instruction takes whole 128-byte
+// lines (8 rows x 128 B).  A must be a panel of already normalised bf16 rows with row stride
+// lda, a multiple of 64, zero padded beyond d (the norm kernel above writes it); W rows are read
+// in place.
 //
-// Stage layout: W tile [256 rows][128 B] then A tile [256 rows][128 B]; the 16-byte chunk index
-// is XOR-swizzled with (row/2)%8, which makes the 8 rows x 8 chunks that one load instruction
-// writes (1 KB, lane-linear) and the 32 rows x 1 chunk that a fragment read touches both
-// bank-conflict free.
+// LDS is a ring of five 32 KB slots, each one operand tile [256 rows][128 B]: half-stage 2g is
+// the W tile of stage g, half-stage 2g+1 its A tile, and half-stage h sits in slot h % 5.  The
+// 16-byte chunk index is XOR-swizzled with (row/2)%8, which makes the 8 rows x 8 chunks that one
+// load instruction writes (1 KB, lane-linear) and the 32 rows x 1 chunk that a fragment read
+// touches both bank-conflict free.
 //
-// Schedule of stage g (buffer g%2), four k-slices of 16; fragments alternate between two
-// register sets, and the barrier sits before the last slice so that no LDS latency hides behind it:
-//   slices 0..2: MFMAs on the slice's fragments (already in registers), interleaved with the LDS
-//                reads of the next slice's fragments;
-//   wait + barrier: stage g+1 has landed for everyone, and everyone holds the last slice of
-//                stage g in registers, so buffer g%2 is free;
-//   slice 3    : its MFMAs, interleaved with the 16 loads of stage g+2 into buffer g%2 and the LDS
-//                reads of slice 0 of stage g+1.
-// The ring is fed unconditionally and runs on across vocabulary tiles (the next tile's first
-// stage loads under the epilogue); past the last real stage it re-fetches the last tile, never
-// consumed, which keeps the count of loads in flight, and with it the s_waitcnt, constant.
+// Schedule of stage g, four k-slices of 16; fragments alternate between two register sets, and
+// the barrier sits before the last slice so that no LDS latency hides behind it:
+//   slice 0    : MFMAs on its fragments (already in registers), interleaved with the LDS reads of
+//                slice 1 and the 8 loads of the W tile of stage g+2 (into the slot that the A
+//                tile of stage g-1 left at the previous barrier);
+//   slices 1, 2: MFMAs, interleaved with the LDS reads of the next slice;
+//   wait + barrier: both tiles of stage g+1 have landed for everyone (only the W tile just sent
+//                may still be in flight), and everyone holds the last slice of stage g in
+//                registers, so the two slots of stage g are free;
+//   slice 3    : its MFMAs, interleaved with the 8 loads of the A tile of stage g+2 (into the slot
+//                of the W tile of stage g) and the LDS reads of slice 0 of stage g+1.
+// One load per MFMA pair keeps the wavefront's issue slots free for the matrix pipe, and with
+// five slots for two tiles per stage the load pipe always has a tile in flight when it is
+// refilled.  The ring is fed unconditionally and runs on across vocabulary tiles (the next
+// tile's first stages load under the epilogue); past the last real stage it re-fetches the last
+// tile, never consumed, which keeps the count of loads in flight, and with it the s_waitcnt,
+// constant.
 // ---------------------------------------------------------------------------------------
 constexpr int DK = 64;
-constexpr int NST = 2;
-constexpr int STAGE_BYTES = (BM + BN) * DK * 2;
-constexpr int LOADS_PER_STAGE = 16;   // per wavefront: 8 W segments + 8 A segments of 1 KB
+constexpr int SLOTS = 5;
+constexpr int SLOT_BYTES = 256 * DK * 2;
+constexpr int LOADS_PER_TILE = 8;    // per wavefront: 8 segments of 1 KB of one operand tile
 // s_waitcnt immediate (gfx9 layout): vmcnt in bits 3:0 and 15:14, expcnt 6:4 (7 = no wait), lgkmcnt 11:8.
 constexpr int waitcnt_imm(int vmcnt, int lgkmcnt) { return (vmcnt & 0xF) | ((vmcnt >> 4) << 14) | 0x70 | (lgkmcnt << 8); }
 
@@ -470,6 +477,36 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 #define LL_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 #define LL_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+
+// One global_load_lds_dwordx4: every lane fetches 16 bytes from base + off and the wavefront's
+// 1 KB lands lane-linear at LDS byte address lds_dst (wave-uniform, passed in M0).  Written as
+// instructions rather than through the builtin: the compiler cannot tell which LDS bytes a
+// builtin load-to-LDS writes, so it makes every later LDS read wait for ALL loads in flight,
+// which would serialise the ring; here all waits are the explicit s_waitcnt of the main loop.
+__device__ __forceinline__ void load_to_lds_16(const unsigned char* base, unsigned off, unsigned lds_dst) {
+  unsigned saved_m0;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %3\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved_m0)
+      : "v"(off), "s"(base), "s"(lds_dst)
+      : "memory");
+}
+
+// Position of an operand stream in the sweep: vocabulary tile, K step, ring slot.
+struct StreamPos {
+  int tile, kt, slot;
+  __device__ __forceinline__ void advance(int KT) {
+    slot = slot + 2 >= SLOTS ? slot + 2 - SLOTS : slot + 2;   // the same operand, one stage on
+    if (++kt == KT) {
+      kt = 0;
+      ++tile;
+    }
+  }
+};
 
 template <int KR>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
@@ -491,7 +528,7 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   const int KT = lda / DK;
 
   // --- DMA map.  One load instruction fills 8 rows x 128 B; lane l lands at row l/8, physical
-  // chunk l%8.  Wavefront w fills rows [64w, 64w+64) of both tiles in 8 segments; segment s holds
+  // chunk l%8.  Wavefront w fills rows [64w, 64w+64) of a tile in 8 segments; segment s holds
   // rows 64w + 8s + l/8, whose swizzle is (l/16 + 4s) % 8, so the lane fetches logical chunk
   // (l%8) ^ (l/16) ^ 4(s%2).  Addresses are a wave-uniform base plus a 32-bit byte offset.
   const int seg_row = 64 * wave + (lane >> 3);                        // + 8 s
@@ -500,35 +537,41 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   const unsigned char* a_base = reinterpret_cast<const unsigned char*>(p.A + (int64_t)rb * BN * lda);
   const int a_last = p.rows - 1 - rb * BN;                            // last valid row of this block
 
-  int i_tile = tile0, i_kt = 0, i_buf = 0;                            // next stage to issue
+  // Per-lane byte offsets of the 8 segment rows, fixed for the whole sweep (W: per vocabulary tile,
+  // because the last tile clamps its rows to V-1), so that one load costs one address add.
+  unsigned a_row_off[8], w_row_off[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) a_row_off[s] = (unsigned)(min(seg_row + 8 * s, a_last) * lda) * 2u;
+  auto set_w_rows = [&](int tile) {
+    const int w_last = V - 1 - tile * BM;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) w_row_off[s] = (unsigned)(min(seg_row + 8 * s, w_last) * d) * 2u;
+  };
+
+  StreamPos iw = {tile0, 0, 0};   // next W tile to issue (half-stage 2g -> slot 2g % 5)
+  StreamPos ia = {tile0, 0, 1};   // next A tile to issue (half-stage 2g+1)
   const unsigned char* w_base = nullptr;
-  int w_last = 0, i_k0 = 0;
-  auto issue_begin = [&]() {
-    const int t = i_tile < tile1 ? i_tile : tile1 - 1;
+  unsigned w_k[2], a_k[2];        // byte offset of the lane's chunk in the K step, even / odd segments
+  auto begin_w = [&]() {
+    const int t = iw.tile < tile1 ? iw.tile : tile1 - 1;
+    if (iw.kt == 0) set_w_rows(t);
     w_base = reinterpret_cast<const unsigned char*>(p.W + (int64_t)t * BM * d);
-    w_last = V - 1 - t * BM;
-    i_k0 = i_kt * DK;
+    // beyond d the A panel is zero: any finite W chunk will do
+    w_k[0] = (unsigned)min(iw.kt * DK + seg_koff0, d - 8) * 2u;
+    w_k[1] = (unsigned)min(iw.kt * DK + seg_koff1, d - 8) * 2u;
   };
-  // one of the 16 loads of the stage: even n = W segment n/2, odd n = A segment n/2
-  auto issue_one = [&](int n) {
-    unsigned char* stage = smem + i_buf * STAGE_BYTES + (64 * wave) * (DK * 2);
-    const int s = n >> 1;
-    const int ko = i_k0 + ((s & 1) ? seg_koff1 : seg_koff0);
-    if ((n & 1) == 0) {
-      const int wk = ko < d - 8 ? ko : d - 8;   // beyond d the A panel is zero: any finite W chunk will do
-      const unsigned off = (unsigned)(min(seg_row + 8 * s, w_last) * d + wk) * 2u;
-      __builtin_amdgcn_global_load_lds((gptr_t)(w_base + off), (lptr_t)(stage + s * 1024), 16, 0, 0);
-    } else {
-      const unsigned off = (unsigned)(min(seg_row + 8 * s, a_last) * lda + ko) * 2u;
-      __builtin_amdgcn_global_load_lds((gptr_t)(a_base + off), (lptr_t)(stage + BM * DK * 2 + s * 1024), 16, 0, 0);
-    }
+  auto begin_a = [&]() {
+    a_k[0] = (unsigned)(ia.kt * DK + seg_koff0) * 2u;
+    a_k[1] = (unsigned)(ia.kt * DK + seg_koff1) * 2u;
   };
-  auto issue_end = [&]() {
-    i_buf ^= 1;
-    if (++i_kt == KT) {
-      i_kt = 0;
-      ++i_tile;
-    }
+  const unsigned lds_base = (unsigned)(uintptr_t)(lptr_t)smem;
+  auto issue_w = [&](int s) {     // segment s of the W tile at iw
+    const unsigned dst = lds_base + iw.slot * SLOT_BYTES + (64 * wave + 8 * s) * (DK * 2);
+    load_to_lds_16(w_base, w_row_off[s] + w_k[s & 1], dst);
+  };
+  auto issue_a = [&](int s) {     // segment s of the A tile at ia
+    const unsigned dst = lds_base + ia.slot * SLOT_BYTES + (64 * wave + 8 * s) * (DK * 2);
+    load_to_lds_16(a_base, a_row_off[s] + a_k[s & 1], dst);
   };
 
   // --- MFMA fragment map: lane reads row (lane % 32) of each 32-row group; k-slice s is the
@@ -539,26 +582,33 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   int f_off[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) f_off[s] = f_row * (DK * 2) + (((2 * s + f_half) ^ f_swz) * 16);
-  const int a_tile_off = BM * DK * 2 + (wave * 64) * (DK * 2);
+  const int a_wave_off = (wave * 64) * (DK * 2);
 
   const int my_row = rb * BN + tid;
   RowState<KR> st;
   st.init();
   st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
 
-  // prologue: both buffers in flight, the first one landed and its slice-0 fragments read
+  // prologue: W0 A0 W1 A1 in flight; stage 0 landed and its slice-0 fragments read
 #pragma unroll
-  for (int s = 0; s < NST; ++s) {
-    issue_begin();
+  for (int h = 0; h < 4; ++h) {
+    if ((h & 1) == 0) {
+      begin_w();
 #pragma unroll
-    for (int n = 0; n < LOADS_PER_STAGE; ++n) issue_one(n);
-    issue_end();
+      for (int s = 0; s < LOADS_PER_TILE; ++s) issue_w(s);
+      iw.advance(KT);
+    } else {
+      begin_a();
+#pragma unroll
+      for (int s = 0; s < LOADS_PER_TILE; ++s) issue_a(s);
+      ia.advance(KT);
+    }
   }
-  __builtin_amdgcn_s_waitcnt(waitcnt_imm(LOADS_PER_STAGE, 15));   // stage 0 landed
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE, 15));   // W0 and A0 landed
   __syncthreads();
   bf16x8 fa0[2], fw0[8], fa1[2], fw1[8];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) fa0[j] = *reinterpret_cast<const bf16x8*>(smem + a_tile_off + j * 32 * (DK * 2) + f_off[0]);
+  for (int j = 0; j < 2; ++j) fa0[j] = *reinterpret_cast<const bf16x8*>(smem + SLOT_BYTES + a_wave_off + j * 32 * (DK * 2) + f_off[0]);
 #pragma unroll
   for (int i = 0; i < 8; ++i) fw0[i] = *reinterpret_cast<const bf16x8*>(smem + i * 32 * (DK * 2) + f_off[0]);
 
@@ -582,7 +632,7 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
     LL_SCHED_FENCE();                                                                               \
   }
 
-  int buf = 0;
+  int w_slot = 0;   // slot of the W tile being consumed; its A tile is in the next slot
   for (int tile = tile0; tile < tile1; ++tile) {
     f32x16 acc[8][2];
 #pragma unroll
@@ -593,21 +643,28 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     for (int kt = 0; kt < KT; ++kt) {
-      const unsigned char* sW = smem + buf * STAGE_BYTES;
-      const unsigned char* sA = sW + a_tile_off;
-      buf ^= 1;
-      const unsigned char* nW = smem + buf * STAGE_BYTES;
-      const unsigned char* nA = nW + a_tile_off;
+      const int a_slot = w_slot + 1 >= SLOTS ? w_slot + 1 - SLOTS : w_slot + 1;
+      const int nw_slot = w_slot + 2 >= SLOTS ? w_slot + 2 - SLOTS : w_slot + 2;
+      const int na_slot = w_slot + 3 >= SLOTS ? w_slot + 3 - SLOTS : w_slot + 3;
+      const unsigned char* sW = smem + w_slot * SLOT_BYTES;
+      const unsigned char* sA = smem + a_slot * SLOT_BYTES + a_wave_off;
+      const unsigned char* nW = smem + nw_slot * SLOT_BYTES;
+      const unsigned char* nA = smem + na_slot * SLOT_BYTES + a_wave_off;
+      w_slot = nw_slot;
 
-      LL_SLICE(fw0, fa0, fw1, fa1, sW, sA, f_off[1], (void)0)
+      // slice 0 also sends off the W tile of stage g+3 (its slot was freed at the last barrier)
+      begin_w();
+      LL_SLICE(fw0, fa0, fw1, fa1, sW, sA, f_off[1], issue_w(i))
+      iw.advance(KT);
       LL_SLICE(fw1, fa1, fw0, fa0, sW, sA, f_off[2], (void)0)
       LL_SLICE(fw0, fa0, fw1, fa1, sW, sA, f_off[3], (void)0)
-      // stage g+1 landed (its loads are the only ones out); all my reads of stage g done
-      __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+      // stage g+1 landed (only the W tile just sent may still be out); all my reads of stage g done
+      __builtin_amdgcn_s_waitcnt(waitcnt_imm(LOADS_PER_TILE, 0));
       __syncthreads();
-      issue_begin();
-      LL_SLICE(fw1, fa1, fw0, fa0, nW, nA, f_off[0], issue_one(2 * i); issue_one(2 * i + 1))
-      issue_end();
+      // slice 3 sends off the A tile of stage g+2 into the slot the W tile of stage g just left
+      begin_a();
+      LL_SLICE(fw1, fa1, fw0, fa0, nW, nA, f_off[0], issue_a(i))
+      ia.advance(KT);
     }
     epilogue_tile(acc, st, tile * BM, V);
   }
@@ -737,7 +794,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   // The direct-to-LDS kernel addresses rows with 32-bit byte offsets from a per-tile base.
   const bool dma_ok = (int64_t)BM * d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * plan.lda * 2 < (int64_t)1 << 31;
   const bool dma = g_gemm_path != 1 && dma_ok;
-  const size_t lds = dma ? (size_t)NST * STAGE_BYTES : (size_t)(BM + BN) * BK * 2;
+  const size_t lds = dma ? (size_t)SLOTS * SLOT_BYTES : (size_t)(BM + BN) * BK * 2;
   // The top-k lists live in registers: the kernels are built for a few list lengths KR >= k.
   void (*kern)(const GemmArgs);
   if (k <= 4)
