@@ -75,6 +75,23 @@ int ll_project(const ll_shape* shape, void* workspace, size_t workspace_bytes,
                void* stream);
 
 /*
+ * ll_project in the paper's own output format.  Same as ll_project, plus:
+ *   bias   fp32 [V] or NULL: the b of Eq. 1, added to every logit before the softmax statistics,
+ *          the top-k selection and the target gather
+ *   flags  LL_FLAG_TOPK_SOFTMAX: out_topk_p holds the softmax over the k selected logits only
+ *          (paper Sec. 3.3, "Top-k extraction": a conditional distribution over the candidates),
+ *          i.e. p_i / sum_{j in top-k} p_j; entropy and target log-prob stay full-vocabulary.
+ *          Any other bit set is LL_EINVAL.
+ */
+#define LL_FLAG_TOPK_SOFTMAX 1u
+int ll_project_ex(const ll_shape* shape, void* workspace, size_t workspace_bytes,
+                  const void* hidden, const void* gamma, const void* W_U, const float* bias,
+                  unsigned flags, float eps, int k, const int32_t* target_ids,
+                  int32_t* out_topk_ids, float* out_topk_p,
+                  float* out_target_logp, float* out_entropy,
+                  void* stream);
+
+/*
  * ll_project with per-phase timing, for benchmarks.  Same arguments and results; in addition
  * phase_ms (HOST pointer, 3 floats) receives the GPU time in milliseconds, summed over the row
  * passes, of {RMS statistics, fused projection kernel, split merge}, measured with HIP events

@@ -104,8 +104,8 @@ def rmsnorm(hidden_bits, gamma_bits, eps: float, round_a: bool = True) -> np.nda
     return a
 
 
-def full_logits(a: np.ndarray, w_bits, slab: int = 8192) -> np.ndarray:
-    """z[r, v] = sum_j a[r, j] * W_out[v, j]  (Eq. 1 with b = 0), fp64 [R, V].
+def full_logits(a: np.ndarray, w_bits, slab: int = 8192, bias=None) -> np.ndarray:
+    """z[r, v] = sum_j a[r, j] * W_out[v, j] + b[v]  (Eq. 1; b = 0 when bias is None), fp64 [R, V].
 
     W_out is widened to fp64 one slab of vocabulary rows at a time so that a
     2 GB bf16 matrix never becomes a 17 GB fp64 one; the slabs are disjoint
@@ -117,6 +117,8 @@ def full_logits(a: np.ndarray, w_bits, slab: int = 8192) -> np.ndarray:
     for v0 in range(0, V, slab):
         w = bf16_bits_to_f64(w_bits[v0:v0 + slab])
         z[:, v0:v0 + slab] = a @ w.T
+    if bias is not None:
+        z += np.asarray(bias, dtype=np.float64)[None, :]
     return z
 
 
@@ -159,10 +161,10 @@ def softmax_summaries(z: np.ndarray, k: int, target_ids=None) -> dict:
 
 
 def lens_project(hidden_bits, gamma_bits, w_bits, eps: float, k: int,
-                 target_ids=None, round_a: bool = True) -> dict:
+                 target_ids=None, round_a: bool = True, bias=None) -> dict:
     """The whole projection for rows hidden_bits [R, d]: Eq. (1), then the summaries."""
     a = rmsnorm(hidden_bits, gamma_bits, eps, round_a=round_a)
-    z = full_logits(a, w_bits)
+    z = full_logits(a, w_bits, bias=bias)
     return softmax_summaries(z, k, target_ids)
 
 

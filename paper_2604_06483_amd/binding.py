@@ -14,6 +14,7 @@ import torch
 
 LL_OK, LL_EINVAL, LL_EWORKSPACE, LL_EHIP = 0, -1, -2, -3
 LL_KMAX = 32
+LL_FLAG_TOPK_SOFTMAX = 1
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libll.so")
 _lib = None
@@ -47,6 +48,8 @@ def lib() -> ctypes.CDLL:
         L.ll_workspace_bytes.restype = c_size_t
         L.ll_project.argtypes = _PROJECT_ARGS
         L.ll_project.restype = c_int
+        L.ll_project_ex.argtypes = _PROJECT_ARGS[:6] + [c_void_p, ctypes.c_uint] + _PROJECT_ARGS[6:]
+        L.ll_project_ex.restype = c_int
         L.ll_project_timed.argtypes = _PROJECT_ARGS + [POINTER(c_float)]
         L.ll_project_timed.restype = c_int
         L.ll_steer_workspace_bytes.argtypes = [c_int32]
@@ -97,8 +100,11 @@ def ll_steer_workspace_bytes(d: int) -> int:
     return int(lib().ll_steer_workspace_bytes(d))
 
 
-def ll_project(hidden, gamma, W_U, eps, k, target_ids=None, *, workspace=None, stream=None, out=None, timed=False):
+def ll_project(hidden, gamma, W_U, eps, k, target_ids=None, *, workspace=None, stream=None, out=None, timed=False,
+               bias=None, topk_softmax=False):
     """hidden [..., d] bf16, gamma [d] bf16 or None, W_U [V, d] bf16, target_ids [N] int32 or None.
+    bias [V] fp32 (the b of Eq. 1) and topk_softmax (probabilities over the k selected logits only, the paper's
+    own output format) go through ll_project_ex.
 
     Returns (topk_ids [N,k] int32, topk_p [N,k] fp32, target_logp [N] fp32 or None, entropy [N] fp32),
     plus the three phase times in ms when timed=True (that variant synchronises the stream).
@@ -127,6 +133,15 @@ def ll_project(hidden, gamma, W_U, eps, k, target_ids=None, *, workspace=None, s
         ids, p, logp, ent = out
     args = [shape, _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(h2), _ptr(gamma), _ptr(W_U),
             float(eps), int(k), _ptr(target_ids), _ptr(ids), _ptr(p), _ptr(logp), _ptr(ent), _stream(stream)]
+    if bias is not None or topk_softmax:
+        if timed:
+            raise ValueError("the timed variant has no bias / top-k-softmax form")
+        if bias is not None:
+            _check(bias, torch.float32, "bias", (V,))
+        rc = lib().ll_project_ex(*args[:6], _ptr(bias), LL_FLAG_TOPK_SOFTMAX if topk_softmax else 0, *args[6:])
+        if rc != LL_OK:
+            raise LLError(rc, "ll_project_ex")
+        return ids, p, logp, ent
     if timed:
         ms = (c_float * 3)()
         rc = lib().ll_project_timed(*args, ms)

@@ -123,6 +123,7 @@ struct GemmArgs {
   const uint16_t* gamma;    // [d] or nullptr
   const uint16_t* W;        // [V, d] bf16
   const int32_t* target;    // [rows] or nullptr
+  const float* bias;        // [V] fp32 or nullptr: the b of Eq. 1
   float4* stats;            // [rows, splits]     (m, S, T, z_target)
   uint2* top;               // [rows, splits, k]  (logit bits, id), sorted
   int64_t lda;              // row stride of A in elements
@@ -207,8 +208,9 @@ __device__ __forceinline__ float select32(const float (&x)[32], int o) {
 }
 
 // Processes vocabulary entries [v0 + 32 I, v0 + 32 I + 32) of the finished tile for the lane's row.
-template <int I, int KR>
-__device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowState<KR>& st, int v0, int V, bool partial) {
+template <int I, int KR, bool BIAS>
+__device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowState<KR>& st, int v0, int V, bool partial,
+                                               const float* __restrict__ bias) {
   // x[o]: logit of vocabulary entry v0 + 32 I + o for this lane's row.  The swap hands the lower
   // lane half the row tile j = 0 and the upper half j = 1, so that lane l owns row 64 w + l.
   float x[32];
@@ -221,6 +223,11 @@ __device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowSta
     x[o + 4] = __uint_as_float(sw[1]);
   }
   const int g0 = v0 + 32 * I;
+  if (BIAS) {   // one coalesced load of the group's 32 biases, then a broadcast per entry
+    const unsigned b = __float_as_uint(bias[min(g0 + (int)(threadIdx.x & 31), V - 1)]);
+#pragma unroll
+    for (int o = 0; o < 32; ++o) x[o] += __uint_as_float(__builtin_amdgcn_readlane(b, o));
+  }
   if (partial) {
 #pragma unroll
     for (int o = 0; o < 32; ++o)
@@ -271,20 +278,21 @@ __device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowSta
   }
 }
 
-template <int KR>
-__device__ __forceinline__ void epilogue_tile(const f32x16 (&acc)[8][2], RowState<KR>& st, int v0, int V) {
+template <int KR, bool BIAS>
+__device__ __forceinline__ void epilogue_tile(const f32x16 (&acc)[8][2], RowState<KR>& st, int v0, int V,
+                                              const float* __restrict__ bias) {
   const bool partial = v0 + BM > V;
   // The accumulators are read below through inline asm, which the compiler's MFMA hazard
   // bookkeeping does not see: let the last MFMA of the tile drain first.
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-  epilogue_group<0>(acc, st, v0, V, partial);
-  epilogue_group<1>(acc, st, v0, V, partial);
-  epilogue_group<2>(acc, st, v0, V, partial);
-  epilogue_group<3>(acc, st, v0, V, partial);
-  epilogue_group<4>(acc, st, v0, V, partial);
-  epilogue_group<5>(acc, st, v0, V, partial);
-  epilogue_group<6>(acc, st, v0, V, partial);
-  epilogue_group<7>(acc, st, v0, V, partial);
+  epilogue_group<0, KR, BIAS>(acc, st, v0, V, partial, bias);
+  epilogue_group<1, KR, BIAS>(acc, st, v0, V, partial, bias);
+  epilogue_group<2, KR, BIAS>(acc, st, v0, V, partial, bias);
+  epilogue_group<3, KR, BIAS>(acc, st, v0, V, partial, bias);
+  epilogue_group<4, KR, BIAS>(acc, st, v0, V, partial, bias);
+  epilogue_group<5, KR, BIAS>(acc, st, v0, V, partial, bias);
+  epilogue_group<6, KR, BIAS>(acc, st, v0, V, partial, bias);
+  epilogue_group<7, KR, BIAS>(acc, st, v0, V, partial, bias);
 }
 
 // Per-(row, split) partial results: (m, S, T, z_target) and the k best (logit bits, id) pairs.
@@ -314,7 +322,7 @@ __device__ __forceinline__ int xcd_logical_block() {
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ int lds_off(int row, int chunk) { return (row * 8 + (chunk ^ ((row >> 1) & 7))) * 16; }
 
-template <int KR>
+template <int KR, bool BIAS>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void ll_lens_gemm_kernel(const GemmArgs p) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -429,7 +437,7 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
       }
     }
-    epilogue_tile(acc, st, v0, V);
+    epilogue_tile<KR, BIAS>(acc, st, v0, V, p.bias);
   }
   epilogue_store(p, st, my_row, split);
 }
@@ -666,7 +674,7 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
       LL_SLICE(fw1, fa1, fw0, fa0, nW, nA, f_off[0], issue_a(i))
       ia.advance(KT);
     }
-    epilogue_tile(acc, st, tile * BM, V);
+    epilogue_tile<KR, false>(acc, st, tile * BM, V, nullptr);
   }
 #undef LL_SLICE
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));   // drain the ring before the LDS is given back
@@ -677,7 +685,7 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
 // a8: merge the splits of each row and finalise.  One thread per row.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict__ stats, const uint2* __restrict__ top,
-                                                       int rows, int splits, int k, int V,
+                                                       int rows, int splits, int k, int V, int topk_softmax,
                                                        const int32_t* __restrict__ target, int32_t* __restrict__ out_ids,
                                                        float* __restrict__ out_p, float* __restrict__ out_logp,
                                                        float* __restrict__ out_entropy) {
@@ -725,7 +733,16 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict_
     for (int s = 0; s < MAX_SPLITS; ++s)
       if (s == bs) ++head[s];
     out_ids[(int64_t)row * k + j] = bi;
-    out_p[(int64_t)row * k + j] = __builtin_amdgcn_exp2f(((bz - M) - logS) * LOG2E);
+    out_p[(int64_t)row * k + j] = topk_softmax ? bz : __builtin_amdgcn_exp2f(((bz - M) - logS) * LOG2E);
+  }
+  if (topk_softmax) {
+    // The paper's own probabilities (Sec. 3.3): a softmax over the k selected logits only.
+    float* zp = out_p + (int64_t)row * k;
+    const float z0 = zp[0];   // the largest
+    float sk = 0.f;
+    for (int j = 0; j < k; ++j) sk += __builtin_amdgcn_exp2f((zp[j] - z0) * LOG2E);
+    const float inv = 1.0f / sk;
+    for (int j = 0; j < k; ++j) zp[j] = __builtin_amdgcn_exp2f((zp[j] - z0) * LOG2E) * inv;
   }
 }
 
@@ -766,7 +783,8 @@ Plan make_plan(const ll_shape* s, int k) {
 int g_gemm_path = 0;
 
 int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
-                 const void* W_U, float eps, int k, const int32_t* target_ids, int32_t* out_topk_ids, float* out_topk_p,
+                 const void* W_U, const float* bias, unsigned flags, float eps, int k, const int32_t* target_ids,
+                 int32_t* out_topk_ids, float* out_topk_p,
                  float* out_target_logp, float* out_entropy, hipStream_t stream, float* phase_ms) {
   if (!shape_ok(shape, k)) return LL_EINVAL;
   if (shape->N == 0) {
@@ -777,6 +795,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     return LL_EINVAL;
   if (target_ids != nullptr && out_target_logp == nullptr) return LL_EINVAL;
   if (!(eps >= 0.f)) return LL_EINVAL;
+  if ((flags & ~(unsigned)LL_FLAG_TOPK_SOFTMAX) != 0 || ((uintptr_t)bias & 3)) return LL_EINVAL;
   const uintptr_t align_or = (uintptr_t)hidden | (uintptr_t)W_U | (uintptr_t)gamma;
   if (align_or & 15) return LL_EINVAL;
   const Plan plan = make_plan(shape, k);
@@ -793,18 +812,23 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   const bool has_gamma = gamma != nullptr;
   // The direct-to-LDS kernel addresses rows with 32-bit byte offsets from a per-tile base.
   const bool dma_ok = (int64_t)BM * d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * plan.lda * 2 < (int64_t)1 << 31;
-  const bool dma = g_gemm_path != 1 && dma_ok;
+  // A bias (rare: the paper's model families have none) goes through the register-staged kernel,
+  // so that the fast kernel carries no code or registers for it.
+  const bool dma = g_gemm_path != 1 && dma_ok && bias == nullptr;
   const size_t lds = dma ? (size_t)SLOTS * SLOT_BYTES : (size_t)(BM + BN) * BK * 2;
   // The top-k lists live in registers: the kernels are built for a few list lengths KR >= k.
   void (*kern)(const GemmArgs);
+#define LL_PICK(KR) \
+  (dma ? ll_lens_gemm_dma_kernel<KR> : (bias ? ll_lens_gemm_kernel<KR, true> : ll_lens_gemm_kernel<KR, false>))
   if (k <= 4)
-    kern = dma ? ll_lens_gemm_dma_kernel<4> : ll_lens_gemm_kernel<4>;
+    kern = LL_PICK(4);
   else if (k <= 12)
-    kern = dma ? ll_lens_gemm_dma_kernel<12> : ll_lens_gemm_kernel<12>;
+    kern = LL_PICK(12);
   else if (k <= 20)
-    kern = dma ? ll_lens_gemm_dma_kernel<20> : ll_lens_gemm_kernel<20>;
+    kern = LL_PICK(20);
   else
-    kern = dma ? ll_lens_gemm_dma_kernel<32> : ll_lens_gemm_kernel<32>;
+    kern = LL_PICK(32);
+#undef LL_PICK
   LL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   // The direct-to-LDS kernel reads hidden in place when the rows need neither scaling nor padding.
   const bool need_panel = dma && (has_gamma || plan.lda != d);
@@ -863,6 +887,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     a.gamma = static_cast<const uint16_t*>(gamma);
     a.W = static_cast<const uint16_t*>(W_U);
     a.target = target_ids ? target_ids + r0 : nullptr;
+    a.bias = bias;
     a.stats = stats;
     a.top = top;
     a.rows = rows;
@@ -878,7 +903,8 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     LL_CHECK_F(hipGetLastError());
     LL_CHECK_F(mark());
     hipLaunchKernelGGL(ll_merge_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, (const float4*)stats, (const uint2*)top,
-                       rows, splits, k, V, a.target, out_topk_ids + r0 * k, out_topk_p + r0 * k,
+                       rows, splits, k, V, (flags & LL_FLAG_TOPK_SOFTMAX) ? 1 : 0, a.target, out_topk_ids + r0 * k,
+                       out_topk_p + r0 * k,
                        out_target_logp ? out_target_logp + r0 : nullptr, out_entropy + r0);
     LL_CHECK_F(hipGetLastError());
     LL_CHECK_F(mark());
@@ -919,16 +945,23 @@ size_t ll_workspace_bytes(const ll_shape* shape, int k) {
 int ll_project(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
                const void* W_U, float eps, int k, const int32_t* target_ids, int32_t* out_topk_ids, float* out_topk_p,
                float* out_target_logp, float* out_entropy, void* stream) {
-  return project_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, eps, k, target_ids, out_topk_ids, out_topk_p,
-                      out_target_logp, out_entropy, static_cast<hipStream_t>(stream), nullptr);
+  return project_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, nullptr, 0u, eps, k, target_ids, out_topk_ids,
+                      out_topk_p, out_target_logp, out_entropy, static_cast<hipStream_t>(stream), nullptr);
+}
+
+int ll_project_ex(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
+                  const void* W_U, const float* bias, unsigned flags, float eps, int k, const int32_t* target_ids,
+                  int32_t* out_topk_ids, float* out_topk_p, float* out_target_logp, float* out_entropy, void* stream) {
+  return project_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, bias, flags, eps, k, target_ids, out_topk_ids,
+                      out_topk_p, out_target_logp, out_entropy, static_cast<hipStream_t>(stream), nullptr);
 }
 
 int ll_project_timed(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
                      const void* W_U, float eps, int k, const int32_t* target_ids, int32_t* out_topk_ids, float* out_topk_p,
                      float* out_target_logp, float* out_entropy, void* stream, float* phase_ms) {
   if (phase_ms == nullptr) return LL_EINVAL;
-  return project_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, eps, k, target_ids, out_topk_ids, out_topk_p,
-                      out_target_logp, out_entropy, static_cast<hipStream_t>(stream), phase_ms);
+  return project_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, nullptr, 0u, eps, k, target_ids, out_topk_ids,
+                      out_topk_p, out_target_logp, out_entropy, static_cast<hipStream_t>(stream), phase_ms);
 }
 
 }  // extern "C"

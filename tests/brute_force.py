@@ -28,7 +28,7 @@ def round_to_bf16(x: float) -> float:
     return math.copysign(r, x)
 
 
-def project_row(h, gamma, W, eps, k, target, round_a=True):
+def project_row(h, gamma, W, eps, k, target, round_a=True, bias=None):
     """One lens row.  h [d], gamma [d] or None, W [V][d] (lists of floats).
 
     Returns dict(ids, p, logits, lse, entropy, target_logp).
@@ -42,7 +42,7 @@ def project_row(h, gamma, W, eps, k, target, round_a=True):
         a = [gamma[j] * h[j] / math.sqrt(ms + eps) for j in range(d)]
         if round_a:
             a = [round_to_bf16(x) for x in a]
-    z = [math.fsum(a[j] * W[v][j] for j in range(d)) for v in range(V)]
+    z = [math.fsum([a[j] * W[v][j] for j in range(d)] + ([bias[v]] if bias is not None else [])) for v in range(V)]
     zmax = max(z)
     lse = zmax + math.log(math.fsum(math.exp(x - zmax) for x in z))
     p = [math.exp(x - lse) for x in z]

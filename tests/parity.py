@@ -16,10 +16,10 @@ TOL_P = 1e-3
 TIE_BAND = 1e-3
 
 
-def oracle_rows(hidden_bits, gamma_bits, w_bits, eps, k, target_ids, round_a=True):
+def oracle_rows(hidden_bits, gamma_bits, w_bits, eps, k, target_ids, round_a=True, bias=None):
     """Oracle summaries plus the full logits of the given rows."""
     a = O.rmsnorm(hidden_bits, gamma_bits, eps, round_a=round_a)
-    z = O.full_logits(a, w_bits)
+    z = O.full_logits(a, w_bits, bias=bias)
     out = O.softmax_summaries(z, k, target_ids)
     out["z"] = z
     return out

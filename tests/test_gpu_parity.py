@@ -167,6 +167,39 @@ def test_no_target_and_prenormalised_rows():
     P.compare(got, ref, cfg.k, label="gamma-null")
 
 
+def test_paper_output_format_bias_and_topk_softmax():
+    """ll_project_ex: the b of Eq. (1), and probabilities over the k selected logits only (paper Sec. 3.3)."""
+    say("ll_project_ex: bias + top-k-only softmax")
+    cfg = WL.LensConfig("ex", L=2, T=150, d=320, V=1300, k=3)       # k = 3 as in the paper's heatmap figure
+    w = WL.make_workload(cfg, DEV, seed=8)
+    g = torch.Generator(device=DEV).manual_seed(3)
+    bias = torch.randn((cfg.V,), generator=g, device=DEV) * 0.5
+    rows = np.arange(cfg.N)
+    hb, gb, wb = WL.bf16_bits(w.hidden.reshape(-1, cfg.d)), WL.bf16_bits(w.gamma), WL.bf16_bits(w.W_U)
+    t = w.target_ids.cpu().numpy()
+    ref = P.oracle_rows(hb, gb, wb, cfg.eps, cfg.k, t, bias=bias.cpu().numpy())
+    # bias only: full-softmax probabilities
+    res = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, bias=bias)
+    torch.cuda.synchronize()
+    P.compare(P.to_numpy(res), ref, cfg.k, label="bias")
+    # bias + the paper's probabilities
+    res = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, bias=bias, topk_softmax=True)
+    torch.cuda.synchronize()
+    got = P.to_numpy(res)
+    want_p = O.topk_renormalised(ref["topk_p"])
+    assert np.max(np.abs(got["topk_p"] - want_p)) <= P.TOL_P
+    np.testing.assert_allclose(got["topk_p"].sum(1), 1.0, atol=1e-5)
+    assert np.array_equal(got["topk_ids"], ref["topk_ids"]) or np.mean(got["topk_ids"] != ref["topk_ids"]) < 0.01
+    assert np.max(np.abs(got["entropy"] - ref["entropy"])) <= P.TOL_ENT      # still full-vocabulary
+    assert np.max(np.abs(got["target_logp"] - ref["target_logp"])) <= P.TOL_LOGP
+    # no bias, flag only, equals renormalising the plain result
+    a = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids)
+    b = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, topk_softmax=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0])
+    assert torch.allclose(b[1], a[1] / a[1].sum(1, keepdim=True), atol=1e-6)
+
+
 def test_caller_workspace_and_stream():
     say("caller-provided workspace on a side stream, twice")
     cfg = WL.LensConfig("ws", L=1, T=300, d=192, V=1500, k=4)

@@ -104,6 +104,29 @@ def pin_brute_force(O):
         np.testing.assert_allclose(got["topk_p"][0], want["p"], rtol=1e-12)
 
 
+def pin_bias(O):
+    """Eq. (1) with its b: brute force, and a shift of every logit by a constant changes nothing but the logits."""
+    h, g, W, t = rand_case(41, 3, 8, 13)
+    rng = np.random.default_rng(2)
+    b = rng.standard_normal(13)
+    got = O.lens_project(h, g, W, 1e-5, 4, t, bias=b)
+    hf, gf, Wf = bits_to_float(h), bits_to_float(g), bits_to_float(W)
+    for r in range(3):
+        want = BF.project_row(list(hf[r]), list(gf), [list(w) for w in Wf], 1e-5, 4, int(t[r]), bias=list(b))
+        assert list(got["topk_ids"][r]) == want["ids"]
+        np.testing.assert_allclose(got["topk_p"][r], want["p"], rtol=1e-12)
+        assert abs(got["entropy"][r] - want["entropy"]) < 1e-12
+        assert abs(got["target_logp"][r] - want["target_logp"]) < 1e-12
+    base = O.lens_project(h, g, W, 1e-5, 4, t)
+    shifted = O.lens_project(h, g, W, 1e-5, 4, t, bias=np.full(13, 2.5))
+    assert np.array_equal(base["topk_ids"], shifted["topk_ids"])
+    np.testing.assert_allclose(base["topk_p"], shifted["topk_p"], rtol=1e-12)
+    np.testing.assert_allclose(shifted["topk_logits"], base["topk_logits"] + 2.5, rtol=1e-12)
+    # a huge bias on one id puts it first
+    b2 = np.zeros(13); b2[7] = 100.0
+    assert np.all(O.lens_project(h, g, W, 1e-5, 4, t, bias=b2)["topk_ids"][:, 0] == 7)
+
+
 def pin_invariants(O):
     h, g, W, t = rand_case(7, 12, 64, 300)
     k = 9
@@ -304,7 +327,7 @@ def pin_steer_inject(O):
     assert np.all(np.diff(np.array(lp), axis=0) > 0)
 
 
-PINS = [pin_bf16_widen, pin_bf16_round, pin_brute_force, pin_invariants, pin_one_hot, pin_zero_row,
+PINS = [pin_bf16_widen, pin_bf16_round, pin_brute_force, pin_bias, pin_invariants, pin_one_hot, pin_zero_row,
         pin_eps_and_gamma, pin_scale_invariance, pin_library_routines, pin_permutation,
         pin_synthetic_entropy_band, pin_topk_renormalised, pin_steer_vector, pin_steer_inject]
 
@@ -387,9 +410,17 @@ def _summaries_variant(kind):
     return f
 
 
-def _logits_transposed(a, w_bits, slab=8192):
+def _logits_transposed(a, w_bits, slab=8192, bias=None):
     w = _real["bf16_bits_to_f64"](w_bits)
-    return a @ w if w.shape[0] == w.shape[1] else _real["full_logits"](a, w_bits)
+    return a @ w if w.shape[0] == w.shape[1] else _real["full_logits"](a, w_bits, bias=bias)
+
+
+def _logits_bias_dropped(a, w_bits, slab=8192, bias=None):
+    return _real["full_logits"](a, w_bits)
+
+
+def _logits_bias_subtracted(a, w_bits, slab=8192, bias=None):
+    return _real["full_logits"](a, w_bits, bias=None if bias is None else -np.asarray(bias))
 
 
 def _steer_variant(kind):
@@ -432,6 +463,8 @@ MUTANTS = {
     "p_is_topk_only_softmax": dict(softmax_summaries=_summaries_variant("topk_only_softmax")),
     "target_logit_not_logp": dict(softmax_summaries=_summaries_variant("unshifted_target")),
     "logits_transposed": dict(full_logits=_logits_transposed),
+    "bias_dropped": dict(full_logits=_logits_bias_dropped),
+    "bias_subtracted": dict(full_logits=_logits_bias_subtracted),
     "steer_sign": dict(steer_vector=_steer_variant("sign")),
     "steer_never_normalised": dict(steer_vector=_steer_variant("never_normalised")),
     "steer_normalise_rows_first": dict(steer_vector=_steer_variant("normalise_rows_first")),
