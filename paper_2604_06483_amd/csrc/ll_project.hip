@@ -486,23 +486,30 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 #define LL_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 #define LL_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
-// One global_load_lds_dwordx4: every lane fetches 16 bytes from base + off and the wavefront's
-// 1 KB lands lane-linear at LDS byte address lds_dst (wave-uniform, passed in M0).  Written as
-// instructions rather than through the builtin: the compiler cannot tell which LDS bytes a
-// builtin load-to-LDS writes, so it makes every later LDS read wait for ALL loads in flight,
-// which would serialise the ring; here all waits are the explicit s_waitcnt of the main loop.
-__device__ __forceinline__ void load_to_lds_16(const unsigned char* base, unsigned off, unsigned lds_dst) {
-  unsigned saved_m0;
-  asm volatile(
-      "s_mov_b32 %0, m0\n\t"
-      "s_mov_b32 m0, %3\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, %2\n\t"
-      "s_mov_b32 m0, %0"
-      : "=&s"(saved_m0)
-      : "v"(off), "s"(base), "s"(lds_dst)
-      : "memory");
+// One global_load_lds_dwordx4: every lane fetches 16 bytes from base + off + IMM and the
+// wavefront's 1 KB lands lane-linear at LDS byte address M0 + IMM (the instruction's immediate
+// offset moves both addresses).  Written as an instruction rather than through the builtin: the
+// compiler cannot tell which LDS bytes a builtin load-to-LDS writes, so it makes every later LDS
+// read wait for ALL loads in flight, which would serialise the ring; here all waits are the
+// explicit s_waitcnt of the main loop.  One instruction per load, with the LDS base set once per
+// tile, matters: a wavefront alone on its SIMD issues one instruction every four cycles or so, and
+// whatever sits between two MFMAs beyond the 32 cycles the first one runs leaves the pipe idle.
+template <int IMM>
+__device__ __forceinline__ void load_to_lds_16(const unsigned char* base, unsigned off) {
+  static_assert(IMM >= -4096 && IMM < 4096, "13-bit signed immediate");
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(off), "s"(base), "n"(IMM) : "memory");
 }
+
+// LDS base of the loads that follow.  M0 is the compiler's own scratch register: it sets it right
+// before each of its own uses and keeps nothing in it, and it knows from the clobber that this
+// statement writes it.  Nothing in the main loop below (MFMA, ds_read, s_waitcnt, s_barrier)
+// makes the compiler use M0, so the value holds from here to the last load of the tile.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void set_lds_dma_base(unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(lds_addr) : "memory", "m0");
+}
+#pragma clang diagnostic pop
 
 // Position of an operand stream in the sweep: vocabulary tile, K step, ring slot.
 struct StreamPos {
@@ -538,49 +545,48 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   // --- DMA map.  One load instruction fills 8 rows x 128 B; lane l lands at row l/8, physical
   // chunk l%8.  Wavefront w fills rows [64w, 64w+64) of a tile in 8 segments; segment s holds
   // rows 64w + 8s + l/8, whose swizzle is (l/16 + 4s) % 8, so the lane fetches logical chunk
-  // (l%8) ^ (l/16) ^ 4(s%2).  Addresses are a wave-uniform base plus a 32-bit byte offset.
+  // (l%8) ^ (l/16) ^ 4(s%2).  M0 points at the middle of the wavefront's 8 KB and segment s uses
+  // the immediate (s-4) KB; since the immediate also moves the global address, the lane's byte
+  // offset carries the opposite shift, plus 7 KB so that it cannot go below zero, and the
+  // wave-uniform base (tile, K step) starts 3 KB early: base + off + imm is the chunk's address.
   const int seg_row = 64 * wave + (lane >> 3);                        // + 8 s
   const int seg_koff0 = ((lane & 7) ^ (lane >> 4)) * 8;               // element offset, even segments
   const int seg_koff1 = seg_koff0 ^ 32;                               // odd segments
-  const unsigned char* a_base = reinterpret_cast<const unsigned char*>(p.A + (int64_t)rb * BN * lda);
   const int a_last = p.rows - 1 - rb * BN;                            // last valid row of this block
+  constexpr int IMM_BIAS = 3072;                                      // largest immediate, segment 7
 
-  // Per-lane byte offsets of the 8 segment rows, fixed for the whole sweep (W: per vocabulary tile,
-  // because the last tile clamps its rows to V-1), so that one load costs one address add.
-  unsigned a_row_off[8], w_row_off[8];
+  // Per-lane byte offsets of the 8 segments, fixed for the whole sweep (W: per vocabulary tile,
+  // because the last tile clamps its rows to V-1): one load is one instruction.
+  unsigned a_off[8], w_off[8];
 #pragma unroll
-  for (int s = 0; s < 8; ++s) a_row_off[s] = (unsigned)(min(seg_row + 8 * s, a_last) * lda) * 2u;
+  for (int s = 0; s < 8; ++s)
+    a_off[s] = (unsigned)(min(seg_row + 8 * s, a_last) * lda + ((s & 1) ? seg_koff1 : seg_koff0)) * 2u + (7168u - 1024u * s);
   auto set_w_rows = [&](int tile) {
     const int w_last = V - 1 - tile * BM;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) w_row_off[s] = (unsigned)(min(seg_row + 8 * s, w_last) * d) * 2u;
+    for (int s = 0; s < 8; ++s)
+      w_off[s] = (unsigned)(min(seg_row + 8 * s, w_last) * d + ((s & 1) ? seg_koff1 : seg_koff0)) * 2u + (7168u - 1024u * s);
   };
 
   StreamPos iw = {tile0, 0, 0};   // next W tile to issue (half-stage 2g -> slot 2g % 5)
   StreamPos ia = {tile0, 0, 1};   // next A tile to issue (half-stage 2g+1)
   const unsigned char* w_base = nullptr;
-  unsigned w_k[2], a_k[2];        // byte offset of the lane's chunk in the K step, even / odd segments
+  const unsigned char* a_base = nullptr;
+  const unsigned lds_mid = (unsigned)(uintptr_t)(lptr_t)smem + wave * (64 * DK * 2) + 4096;
   auto begin_w = [&]() {
     const int t = iw.tile < tile1 ? iw.tile : tile1 - 1;
     if (iw.kt == 0) set_w_rows(t);
-    w_base = reinterpret_cast<const unsigned char*>(p.W + (int64_t)t * BM * d);
-    // beyond d the A panel is zero: any finite W chunk will do
-    w_k[0] = (unsigned)min(iw.kt * DK + seg_koff0, d - 8) * 2u;
-    w_k[1] = (unsigned)min(iw.kt * DK + seg_koff1, d - 8) * 2u;
+    w_base = reinterpret_cast<const unsigned char*>(p.W + (int64_t)t * BM * d + iw.kt * DK) - IMM_BIAS;
+    set_lds_dma_base(lds_mid + iw.slot * SLOT_BYTES);
   };
   auto begin_a = [&]() {
-    a_k[0] = (unsigned)(ia.kt * DK + seg_koff0) * 2u;
-    a_k[1] = (unsigned)(ia.kt * DK + seg_koff1) * 2u;
+    a_base = reinterpret_cast<const unsigned char*>(p.A + (int64_t)rb * BN * lda + ia.kt * DK) - IMM_BIAS;
+    set_lds_dma_base(lds_mid + ia.slot * SLOT_BYTES);
   };
-  const unsigned lds_base = (unsigned)(uintptr_t)(lptr_t)smem;
-  auto issue_w = [&](int s) {     // segment s of the W tile at iw
-    const unsigned dst = lds_base + iw.slot * SLOT_BYTES + (64 * wave + 8 * s) * (DK * 2);
-    load_to_lds_16(w_base, w_row_off[s] + w_k[s & 1], dst);
-  };
-  auto issue_a = [&](int s) {     // segment s of the A tile at ia
-    const unsigned dst = lds_base + ia.slot * SLOT_BYTES + (64 * wave + 8 * s) * (DK * 2);
-    load_to_lds_16(a_base, a_row_off[s] + a_k[s & 1], dst);
-  };
+#define LL_DMA_W(S) load_to_lds_16<((S) - 4) * 1024>(w_base, w_off[S])
+#define LL_DMA_A(S) load_to_lds_16<((S) - 4) * 1024>(a_base, a_off[S])
+#define LL_DMA_NONE(S) (void)0
+#define LL_DMA_TILE(DMA) DMA(0); DMA(1); DMA(2); DMA(3); DMA(4); DMA(5); DMA(6); DMA(7)
 
   // --- MFMA fragment map: lane reads row (lane % 32) of each 32-row group; k-slice s is the
   // logical 16-byte chunk 2s + lane/32 of the row.
@@ -599,18 +605,13 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
 
   // prologue: W0 A0 W1 A1 in flight; stage 0 landed and its slice-0 fragments read
 #pragma unroll
-  for (int h = 0; h < 4; ++h) {
-    if ((h & 1) == 0) {
-      begin_w();
-#pragma unroll
-      for (int s = 0; s < LOADS_PER_TILE; ++s) issue_w(s);
-      iw.advance(KT);
-    } else {
-      begin_a();
-#pragma unroll
-      for (int s = 0; s < LOADS_PER_TILE; ++s) issue_a(s);
-      ia.advance(KT);
-    }
+  for (int h = 0; h < 2; ++h) {
+    begin_w();
+    LL_DMA_TILE(LL_DMA_W);
+    iw.advance(KT);
+    begin_a();
+    LL_DMA_TILE(LL_DMA_A);
+    ia.advance(KT);
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE, 15));   // W0 and A0 landed
   __syncthreads();
@@ -621,24 +622,33 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   for (int i = 0; i < 8; ++i) fw0[i] = *reinterpret_cast<const bf16x8*>(smem + i * 32 * (DK * 2) + f_off[0]);
 
   // MFMAs of one k-slice from fragment set (fw, fa), with the LDS reads of another slice into
-  // (nw, na) from tiles (tW, tA) slipped in under the first four MFMA pairs, so that the last
-  // read has half a slice to land before the next slice needs it.
-#define LL_SLICE(fw, fa, nw, na, tW, tA, off, EXTRA)                                                \
+  // (nw, na) from tiles (tW, tA) slipped in behind the first eight MFMAs, so that the last read
+  // has half a slice to land before the next slice needs it, and one load-to-LDS behind every
+  // second MFMA.  The fences pin that order: no gap between two MFMAs holds more than a handful of
+  // instructions.
+#define LL_LDS_FRAG(ptr) (*reinterpret_cast<const bf16x8*>(ptr))
+#define LL_PAIR(I, fw, fa, nw, na, tW, tA, off, DMA)                                                \
+  acc[I][0] = LL_MFMA(fw[I], fa[0], acc[I][0]);                                                     \
+  if (I == 0) {                                                                                     \
+    na[0] = LL_LDS_FRAG(tA + (off));                                                                \
+    na[1] = LL_LDS_FRAG(tA + 32 * (DK * 2) + (off));                                                \
+  }                                                                                                 \
+  if (I < 4) nw[(2 * I) & 7] = LL_LDS_FRAG(tW + (2 * I) * 32 * (DK * 2) + (off));                         \
   LL_SCHED_FENCE();                                                                                 \
-  _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                   \
-    acc[i][0] = LL_MFMA(fw[i], fa[0], acc[i][0]);                                                   \
-    acc[i][1] = LL_MFMA(fw[i], fa[1], acc[i][1]);                                                   \
-    EXTRA;                                                                                          \
-    if (i == 0) {                                                                                   \
-      na[0] = *reinterpret_cast<const bf16x8*>(tA + (off));                                         \
-      na[1] = *reinterpret_cast<const bf16x8*>(tA + 32 * (DK * 2) + (off));                         \
-    }                                                                                               \
-    if (i < 4) {                                                                                    \
-      nw[2 * i] = *reinterpret_cast<const bf16x8*>(tW + (2 * i) * 32 * (DK * 2) + (off));           \
-      nw[2 * i + 1] = *reinterpret_cast<const bf16x8*>(tW + (2 * i + 1) * 32 * (DK * 2) + (off));   \
-    }                                                                                               \
-    LL_SCHED_FENCE();                                                                               \
-  }
+  acc[I][1] = LL_MFMA(fw[I], fa[1], acc[I][1]);                                                     \
+  if (I < 4) nw[(2 * I + 1) & 7] = LL_LDS_FRAG(tW + (2 * I + 1) * 32 * (DK * 2) + (off));                 \
+  DMA(I);                                                                                           \
+  LL_SCHED_FENCE();
+#define LL_SLICE(fw, fa, nw, na, tW, tA, off, DMA)                                                  \
+  LL_SCHED_FENCE();                                                                                 \
+  LL_PAIR(0, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
+  LL_PAIR(1, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
+  LL_PAIR(2, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
+  LL_PAIR(3, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
+  LL_PAIR(4, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
+  LL_PAIR(5, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
+  LL_PAIR(6, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
+  LL_PAIR(7, fw, fa, nw, na, tW, tA, off, DMA)
 
   int w_slot = 0;   // slot of the W tile being consumed; its A tile is in the next slot
   for (int tile = tile0; tile < tile1; ++tile) {
@@ -662,21 +672,27 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
 
       // slice 0 also sends off the W tile of stage g+3 (its slot was freed at the last barrier)
       begin_w();
-      LL_SLICE(fw0, fa0, fw1, fa1, sW, sA, f_off[1], issue_w(i))
+      LL_SLICE(fw0, fa0, fw1, fa1, sW, sA, f_off[1], LL_DMA_W)
       iw.advance(KT);
-      LL_SLICE(fw1, fa1, fw0, fa0, sW, sA, f_off[2], (void)0)
-      LL_SLICE(fw0, fa0, fw1, fa1, sW, sA, f_off[3], (void)0)
+      LL_SLICE(fw1, fa1, fw0, fa0, sW, sA, f_off[2], LL_DMA_NONE)
+      LL_SLICE(fw0, fa0, fw1, fa1, sW, sA, f_off[3], LL_DMA_NONE)
       // stage g+1 landed (only the W tile just sent may still be out); all my reads of stage g done
       __builtin_amdgcn_s_waitcnt(waitcnt_imm(LOADS_PER_TILE, 0));
       __syncthreads();
       // slice 3 sends off the A tile of stage g+2 into the slot the W tile of stage g just left
       begin_a();
-      LL_SLICE(fw1, fa1, fw0, fa0, nW, nA, f_off[0], issue_a(i))
+      LL_SLICE(fw1, fa1, fw0, fa0, nW, nA, f_off[0], LL_DMA_A)
       ia.advance(KT);
     }
     epilogue_tile<KR, false>(acc, st, tile * BM, V, nullptr);
   }
 #undef LL_SLICE
+#undef LL_PAIR
+#undef LL_LDS_FRAG
+#undef LL_DMA_TILE
+#undef LL_DMA_NONE
+#undef LL_DMA_A
+#undef LL_DMA_W
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));   // drain the ring before the LDS is given back
   epilogue_store(p, st, my_row, split);
 }
@@ -811,7 +827,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   const int d = shape->d, V = shape->V;
   const bool has_gamma = gamma != nullptr;
   // The direct-to-LDS kernel addresses rows with 32-bit byte offsets from a per-tile base.
-  const bool dma_ok = (int64_t)BM * d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * plan.lda * 2 < (int64_t)1 << 31;
+  const bool dma_ok = d % DK == 0 && (int64_t)BM * d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * plan.lda * 2 < (int64_t)1 << 31;
   // A bias (rare: the paper's model families have none) goes through the register-staged kernel,
   // so that the fast kernel carries no code or registers for it.
   const bool dma = g_gemm_path != 1 && dma_ok && bias == nullptr;
