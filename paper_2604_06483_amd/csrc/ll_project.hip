@@ -511,18 +511,6 @@ __device__ __forceinline__ void set_lds_dma_base(unsigned lds_addr) {
 }
 #pragma clang diagnostic pop
 
-// Position of an operand stream in the sweep: vocabulary tile, K step, ring slot.
-struct StreamPos {
-  int tile, kt, slot;
-  __device__ __forceinline__ void advance(int KT) {
-    slot = slot + 2 >= SLOTS ? slot + 2 - SLOTS : slot + 2;   // the same operand, one stage on
-    if (++kt == KT) {
-      kt = 0;
-      ++tile;
-    }
-  }
-};
-
 template <int KR>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void ll_lens_gemm_dma_kernel(const GemmArgs p) {
@@ -568,24 +556,50 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
       w_off[s] = (unsigned)(min(seg_row + 8 * s, w_last) * d + ((s & 1) ? seg_koff1 : seg_koff0)) * 2u + (7168u - 1024u * s);
   };
 
-  StreamPos iw = {tile0, 0, 0};   // next W tile to issue (half-stage 2g -> slot 2g % 5)
-  StreamPos ia = {tile0, 0, 1};   // next A tile to issue (half-stage 2g+1)
-  const unsigned char* w_base = nullptr;
-  const unsigned char* a_base = nullptr;
+  // Producer state of the two operand streams.  Half-stage h (W tile of stage g: h = 2g, its A
+  // tile: h = 2g+1) goes to slot h % 5, so each stream moves on by two slots per stage.  All of it
+  // is wave-uniform and moves on by a few scalar instructions per stage.
   const unsigned lds_mid = (unsigned)(uintptr_t)(lptr_t)smem + wave * (64 * DK * 2) + 4096;
-  auto begin_w = [&]() {
-    const int t = iw.tile < tile1 ? iw.tile : tile1 - 1;
-    if (iw.kt == 0) set_w_rows(t);
-    w_base = reinterpret_cast<const unsigned char*>(p.W + (int64_t)t * BM * d + iw.kt * DK) - IMM_BIAS;
-    set_lds_dma_base(lds_mid + iw.slot * SLOT_BYTES);
+  const unsigned lds_wrap = lds_mid + SLOTS * SLOT_BYTES;
+  const unsigned char* const a_base0 = reinterpret_cast<const unsigned char*>(p.A + (int64_t)rb * BN * lda) - IMM_BIAS;
+  auto w_tile_base = [&](int tile) {
+    return reinterpret_cast<const unsigned char*>(p.W + (int64_t)tile * BM * d) - IMM_BIAS;
   };
-  auto begin_a = [&]() {
-    a_base = reinterpret_cast<const unsigned char*>(p.A + (int64_t)rb * BN * lda + ia.kt * DK) - IMM_BIAS;
-    set_lds_dma_base(lds_mid + ia.slot * SLOT_BYTES);
+  // (LL_PIN_S: the value is computed where the statement stands; without it the compiler gathers
+  // the scalar updates of a whole stage into one lump, and the matrix pipe idles behind it.)
+#define LL_PIN_S(x) asm volatile("" : "+s"(x))
+  int w_tile = tile0, w_kt = 0, a_kt = 0;
+  unsigned w_lds = lds_mid, a_lds = lds_mid + SLOT_BYTES;   // M0 value of the stream's next tile
+  const unsigned char* w_base = w_tile_base(tile0);
+  const unsigned char* a_base = a_base0;
+  set_w_rows(tile0);
+  auto advance_w = [&]() {
+    w_lds += 2 * SLOT_BYTES;
+    if (w_lds >= lds_wrap) w_lds -= SLOTS * SLOT_BYTES;
+    w_base += DK * 2;
+    if (++w_kt == KT) {   // next vocabulary tile; past the end of the sweep the ring refetches the last one
+      w_kt = 0;
+      ++w_tile;
+      const int t = w_tile < tile1 ? w_tile : tile1 - 1;
+      set_w_rows(t);
+      w_base = w_tile_base(t);
+    }
+    LL_PIN_S(w_lds);
+    LL_PIN_S(w_base);
+  };
+  auto advance_a = [&]() {
+    a_lds += 2 * SLOT_BYTES;
+    if (a_lds >= lds_wrap) a_lds -= SLOTS * SLOT_BYTES;
+    a_base += DK * 2;
+    if (++a_kt == KT) {
+      a_kt = 0;
+      a_base = a_base0;
+    }
+    LL_PIN_S(a_lds);
+    LL_PIN_S(a_base);
   };
 #define LL_DMA_W(S) load_to_lds_16<((S) - 4) * 1024>(w_base, w_off[S])
 #define LL_DMA_A(S) load_to_lds_16<((S) - 4) * 1024>(a_base, a_off[S])
-#define LL_DMA_NONE(S) (void)0
 #define LL_DMA_TILE(DMA) DMA(0); DMA(1); DMA(2); DMA(3); DMA(4); DMA(5); DMA(6); DMA(7)
 
   // --- MFMA fragment map: lane reads row (lane % 32) of each 32-row group; k-slice s is the
@@ -603,17 +617,19 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   st.init();
   st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
 
-  // prologue: W0 A0 W1 A1 in flight; stage 0 landed and its slice-0 fragments read
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    begin_w();
-    LL_DMA_TILE(LL_DMA_W);
-    iw.advance(KT);
-    begin_a();
-    LL_DMA_TILE(LL_DMA_A);
-    ia.advance(KT);
-  }
-  __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE, 15));   // W0 and A0 landed
+  // prologue: W0 A0 W1 and the first half of A1 in flight; stage 0 landed
+  set_lds_dma_base(w_lds);
+  LL_DMA_TILE(LL_DMA_W);
+  advance_w();
+  set_lds_dma_base(a_lds);
+  LL_DMA_TILE(LL_DMA_A);
+  advance_a();
+  set_lds_dma_base(w_lds);
+  LL_DMA_TILE(LL_DMA_W);
+  advance_w();
+  set_lds_dma_base(a_lds);
+  LL_DMA_A(0); LL_DMA_A(1); LL_DMA_A(2); LL_DMA_A(3);
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(LOADS_PER_TILE + 4, 15));   // W0 and A0 landed
   __syncthreads();
   bf16x8 fa0[2], fw0[8], fa1[2], fw1[8];
 #pragma unroll
@@ -622,35 +638,84 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   for (int i = 0; i < 8; ++i) fw0[i] = *reinterpret_cast<const bf16x8*>(smem + i * 32 * (DK * 2) + f_off[0]);
 
   // MFMAs of one k-slice from fragment set (fw, fa), with the LDS reads of another slice into
-  // (nw, na) from tiles (tW, tA) slipped in behind the first eight MFMAs, so that the last read
-  // has half a slice to land before the next slice needs it, and one load-to-LDS behind every
-  // second MFMA.  The fences pin that order: no gap between two MFMAs holds more than a handful of
-  // instructions.
+  // (nw, na) from LDS offsets (tW, tA) slipped in behind the first eight MFMAs, so that the last
+  // read has half a slice to land before the next slice needs it.  HOOK(I) is what else goes
+  // behind the second MFMA of pair I: a load-to-LDS or a piece of the streams' bookkeeping.  The
+  // fences pin that order: no gap between two MFMAs holds more than a handful of instructions.
 #define LL_LDS_FRAG(ptr) (*reinterpret_cast<const bf16x8*>(ptr))
-#define LL_PAIR(I, fw, fa, nw, na, tW, tA, off, DMA)                                                \
+#define LL_PAIR(I, fw, fa, nw, na, tW, tA, off, HOOK)                                               \
   acc[I][0] = LL_MFMA(fw[I], fa[0], acc[I][0]);                                                     \
   if (I == 0) {                                                                                     \
-    na[0] = LL_LDS_FRAG(tA + (off));                                                                \
-    na[1] = LL_LDS_FRAG(tA + 32 * (DK * 2) + (off));                                                \
+    na[0] = LL_LDS_FRAG(smem + tA + (off));                                                                \
+    na[1] = LL_LDS_FRAG(smem + tA + 32 * (DK * 2) + (off));                                                \
   }                                                                                                 \
-  if (I < 4) nw[(2 * I) & 7] = LL_LDS_FRAG(tW + (2 * I) * 32 * (DK * 2) + (off));                         \
+  if (I < 4) nw[(2 * I) & 7] = LL_LDS_FRAG(smem + tW + (2 * I) * 32 * (DK * 2) + (off));                         \
   LL_SCHED_FENCE();                                                                                 \
   acc[I][1] = LL_MFMA(fw[I], fa[1], acc[I][1]);                                                     \
-  if (I < 4) nw[(2 * I + 1) & 7] = LL_LDS_FRAG(tW + (2 * I + 1) * 32 * (DK * 2) + (off));                 \
-  DMA(I);                                                                                           \
+  if (I < 4) nw[(2 * I + 1) & 7] = LL_LDS_FRAG(smem + tW + (2 * I + 1) * 32 * (DK * 2) + (off));                 \
+  HOOK(I);                                                                                          \
   LL_SCHED_FENCE();
-#define LL_SLICE(fw, fa, nw, na, tW, tA, off, DMA)                                                  \
+#define LL_SLICE(fw, fa, nw, na, tW, tA, off, HOOK)                                                 \
   LL_SCHED_FENCE();                                                                                 \
-  LL_PAIR(0, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
-  LL_PAIR(1, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
-  LL_PAIR(2, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
-  LL_PAIR(3, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
-  LL_PAIR(4, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
-  LL_PAIR(5, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
-  LL_PAIR(6, fw, fa, nw, na, tW, tA, off, DMA)                                                      \
-  LL_PAIR(7, fw, fa, nw, na, tW, tA, off, DMA)
+  LL_PAIR(0, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
+  LL_PAIR(1, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
+  LL_PAIR(2, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
+  LL_PAIR(3, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
+  LL_PAIR(4, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
+  LL_PAIR(5, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
+  LL_PAIR(6, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
+  LL_PAIR(7, fw, fa, nw, na, tW, tA, off, HOOK)
 
-  int w_slot = 0;   // slot of the W tile being consumed; its A tile is in the next slot
+  // Load schedule of stage g.  The barrier before slice 3 frees the slots of W(g) and A(g); A(g+2)
+  // takes the first (half of it in slice 3, half in slice 0 of the next stage) and W(g+3) the
+  // second (slices 0 to 2 of the next stage), so that no slice sends more than six loads and the
+  // load pipe never sees a burst.  In stage g that reads: slice 0 finishes A(g+1) and starts
+  // W(g+2), slices 1 and 2 finish W(g+2), slice 3 starts A(g+2).  All of A(g+1) is sent before any
+  // of W(g+2), so "all but the last 8 loads have landed" at the barrier covers stage g+1.
+#define LL_HOOK_S0(I)                                \
+  if (I == 0) {                                      \
+    set_lds_dma_base(a_lds);                         \
+    LL_DMA_A(4);                                     \
+  }                                                  \
+  if (I == 1) LL_DMA_A(5);                           \
+  if (I == 2) LL_DMA_A(6);                           \
+  if (I == 3) LL_DMA_A(7);                           \
+  if (I == 4) {                                      \
+    advance_a();                                     \
+    set_lds_dma_base(w_lds);                         \
+  }                                                  \
+  if (I == 5) LL_DMA_W(0);                           \
+  if (I == 6) LL_DMA_W(1);                           \
+  if (I == 7) LL_DMA_W(2)
+#define LL_HOOK_S1(I)                                \
+  if (I == 4) LL_DMA_W(3);                           \
+  if (I == 5) LL_DMA_W(4);                           \
+  if (I == 6) LL_DMA_W(5)
+#define LL_HOOK_S2(I)                                \
+  if (I == 4) LL_DMA_W(6);                           \
+  if (I == 5) LL_DMA_W(7);                           \
+  if (I == 6) advance_w()
+#define LL_HOOK_S3(I)                                \
+  if (I == 3) set_lds_dma_base(a_lds);               \
+  if (I == 4) LL_DMA_A(0);                           \
+  if (I == 5) {                                      \
+    LL_DMA_A(1);                                     \
+    cW = nW;                                         \
+    cA = nA;                                         \
+    nW = nW + 2 * SLOT_BYTES >= RING ? nW + 2 * SLOT_BYTES - RING : nW + 2 * SLOT_BYTES;               \
+    LL_PIN_S(nW);                                    \
+  }                                                  \
+  if (I == 6) {                                      \
+    LL_DMA_A(2);                                     \
+    nA = nA + 2 * SLOT_BYTES >= RING + a_wave_off ? nA + 2 * SLOT_BYTES - RING : nA + 2 * SLOT_BYTES;  \
+    LL_PIN_S(nA);                                    \
+  }                                                  \
+  if (I == 7) LL_DMA_A(3)
+
+  // Consumer state: LDS byte offsets of the W and A tiles of this stage and of the next (the A
+  // offsets include the wavefront's own 64 rows).
+  constexpr int RING = SLOTS * SLOT_BYTES;
+  int cW = 0, cA = SLOT_BYTES + a_wave_off, nW = 2 * SLOT_BYTES, nA = 3 * SLOT_BYTES + a_wave_off;
   for (int tile = tile0; tile < tile1; ++tile) {
     f32x16 acc[8][2];
 #pragma unroll
@@ -661,28 +726,13 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     for (int kt = 0; kt < KT; ++kt) {
-      const int a_slot = w_slot + 1 >= SLOTS ? w_slot + 1 - SLOTS : w_slot + 1;
-      const int nw_slot = w_slot + 2 >= SLOTS ? w_slot + 2 - SLOTS : w_slot + 2;
-      const int na_slot = w_slot + 3 >= SLOTS ? w_slot + 3 - SLOTS : w_slot + 3;
-      const unsigned char* sW = smem + w_slot * SLOT_BYTES;
-      const unsigned char* sA = smem + a_slot * SLOT_BYTES + a_wave_off;
-      const unsigned char* nW = smem + nw_slot * SLOT_BYTES;
-      const unsigned char* nA = smem + na_slot * SLOT_BYTES + a_wave_off;
-      w_slot = nw_slot;
-
-      // slice 0 also sends off the W tile of stage g+3 (its slot was freed at the last barrier)
-      begin_w();
-      LL_SLICE(fw0, fa0, fw1, fa1, sW, sA, f_off[1], LL_DMA_W)
-      iw.advance(KT);
-      LL_SLICE(fw1, fa1, fw0, fa0, sW, sA, f_off[2], LL_DMA_NONE)
-      LL_SLICE(fw0, fa0, fw1, fa1, sW, sA, f_off[3], LL_DMA_NONE)
+      LL_SLICE(fw0, fa0, fw1, fa1, cW, cA, f_off[1], LL_HOOK_S0)
+      LL_SLICE(fw1, fa1, fw0, fa0, cW, cA, f_off[2], LL_HOOK_S1)
+      LL_SLICE(fw0, fa0, fw1, fa1, cW, cA, f_off[3], LL_HOOK_S2)
       // stage g+1 landed (only the W tile just sent may still be out); all my reads of stage g done
       __builtin_amdgcn_s_waitcnt(waitcnt_imm(LOADS_PER_TILE, 0));
       __syncthreads();
-      // slice 3 sends off the A tile of stage g+2 into the slot the W tile of stage g just left
-      begin_a();
-      LL_SLICE(fw1, fa1, fw0, fa0, nW, nA, f_off[0], LL_DMA_A)
-      ia.advance(KT);
+      LL_SLICE(fw1, fa1, fw0, fa0, nW, nA, f_off[0], LL_HOOK_S3)
     }
     epilogue_tile<KR, false>(acc, st, tile * BM, V, nullptr);
   }
@@ -690,7 +740,11 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
 #undef LL_PAIR
 #undef LL_LDS_FRAG
 #undef LL_DMA_TILE
-#undef LL_DMA_NONE
+#undef LL_HOOK_S3
+#undef LL_PIN_S
+#undef LL_HOOK_S2
+#undef LL_HOOK_S1
+#undef LL_HOOK_S0
 #undef LL_DMA_A
 #undef LL_DMA_W
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));   // drain the ring before the LDS is given back
