@@ -449,32 +449,36 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
 // lda, a multiple of 64, zero padded beyond d (the norm kernel above writes it); W rows are read
 // in place.
 //
-// LDS is a ring of five 32 KB slots, each one operand tile [256 rows][128 B]: half-stage 2g is
-// the W tile of stage g, half-stage 2g+1 its A tile, and half-stage h sits in slot h % 5.  The
-// 16-byte chunk index is XOR-swizzled with (row/2)%8, which makes the 8 rows x 8 chunks that one
-// load instruction writes (1 KB, lane-linear) and the 32 rows x 1 chunk that a fragment read
+// LDS holds five 32 KB slots, each one operand tile [256 rows][128 B]: a ring of three for the
+// W tiles (stage g in slot g % 3) and a ring of two for the A tiles (stage g in slot 3 + g % 2).
+// The 16-byte chunk index is XOR-swizzled with (row/2)%8, which makes the 8 rows x 8 chunks that
+// one load instruction writes (1 KB, lane-linear) and the 32 rows x 1 chunk that a fragment read
 // touches both bank-conflict free.
 //
-// Schedule of stage g, four k-slices of 16; fragments alternate between two register sets, and
-// the barrier sits before the last slice so that no LDS latency hides behind it:
-//   slice 0    : MFMAs on its fragments (already in registers), interleaved with the LDS reads of
-//                slice 1 and the 8 loads of the W tile of stage g+2 (into the slot that the A
-//                tile of stage g-1 left at the previous barrier);
-//   slices 1, 2: MFMAs, interleaved with the LDS reads of the next slice;
-//   wait + barrier: both tiles of stage g+1 have landed for everyone (only the W tile just sent
-//                may still be in flight), and everyone holds the last slice of stage g in
-//                registers, so the two slots of stage g are free;
-//   slice 3    : its MFMAs, interleaved with the 8 loads of the A tile of stage g+2 (into the slot
-//                of the W tile of stage g) and the LDS reads of slice 0 of stage g+1.
-// One load per MFMA pair keeps the wavefront's issue slots free for the matrix pipe, and with
-// five slots for two tiles per stage the load pipe always has a tile in flight when it is
-// refilled.  The ring is fed unconditionally and runs on across vocabulary tiles (the next
-// tile's first stages load under the epilogue); past the last real stage it re-fetches the last
-// tile, never consumed, which keeps the count of loads in flight, and with it the s_waitcnt,
-// constant.
+// Wavefront w loads rows [64w, 64w+64) of every tile.  Of a W tile it reads all rows, so W slots
+// change hands at a workgroup barrier; of an A tile it reads exactly the rows it loaded itself,
+// so an A slot is the wavefront's own again as soon as its last fragment of the stage is in
+// registers, with no barrier.  That is what the two rings are for: the A fragments of a whole
+// stage are read early (32 registers), and both streams get about two stages between sending a
+// load and needing its data, from the same 160 KB.
+//
+// Schedule of stage g, four k-slices of 16 (W fragments alternate between two register sets):
+//   slice 0    : MFMAs of k-slice 0; reads the W fragments of k-slice 1 and the A fragments of
+//                k-slice 3 (the last of the stage: the wavefront's rows of A(g)'s slot are free);
+//                sends the second half of W(g+2);
+//   slices 1, 2: MFMAs; read the W fragments of the next k-slice; send A(g+2), half each;
+//   wait + barrier: all loads but the last 16 (W(g+2), A(g+2)) have landed, so stage g+1 is in
+//                LDS for everyone, and everyone holds its last fragments of W(g): that slot is free;
+//   slice 3    : MFMAs; reads the W fragments of k-slice 0 and the A fragments of k-slices 0 to 2
+//                of stage g+1; sends the first half of W(g+3) into the slot of W(g).
+// Four loads per slice, one behind every second MFMA, keep the load pipe evenly fed and the
+// wavefront's issue slots free for the matrix pipe.  The rings are fed unconditionally and run on
+// across vocabulary tiles (the next tile's first stages load under the epilogue); past the last
+// real stage they re-fetch the last tile, never consumed, which keeps the count of loads in
+// flight, and with it the s_waitcnt, constant.
 // ---------------------------------------------------------------------------------------
 constexpr int DK = 64;
-constexpr int SLOTS = 5;
+constexpr int W_SLOTS = 3, A_SLOTS = 2, SLOTS = W_SLOTS + A_SLOTS;
 constexpr int SLOT_BYTES = 256 * DK * 2;
 constexpr int LOADS_PER_TILE = 8;    // per wavefront: 8 segments of 1 KB of one operand tile
 // s_waitcnt immediate (gfx9 layout): vmcnt in bits 3:0 and 15:14, expcnt 6:4 (7 = no wait), lgkmcnt 11:8.
@@ -556,11 +560,11 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
       w_off[s] = (unsigned)(min(seg_row + 8 * s, w_last) * d + ((s & 1) ? seg_koff1 : seg_koff0)) * 2u + (7168u - 1024u * s);
   };
 
-  // Producer state of the two operand streams.  Half-stage h (W tile of stage g: h = 2g, its A
-  // tile: h = 2g+1) goes to slot h % 5, so each stream moves on by two slots per stage.  All of it
-  // is wave-uniform and moves on by a few scalar instructions per stage.
+  // Producer state of the two operand streams, all wave-uniform and moved on by a few scalar
+  // instructions per stage.
   const unsigned lds_mid = (unsigned)(uintptr_t)(lptr_t)smem + wave * (64 * DK * 2) + 4096;
-  const unsigned lds_wrap = lds_mid + SLOTS * SLOT_BYTES;
+  const unsigned w_lds_wrap = lds_mid + W_SLOTS * SLOT_BYTES;
+  const unsigned a_lds_flip = (2 * W_SLOTS + 1) * SLOT_BYTES + 2 * lds_mid;   // slot 3 <-> slot 4
   const unsigned char* const a_base0 = reinterpret_cast<const unsigned char*>(p.A + (int64_t)rb * BN * lda) - IMM_BIAS;
   auto w_tile_base = [&](int tile) {
     return reinterpret_cast<const unsigned char*>(p.W + (int64_t)tile * BM * d) - IMM_BIAS;
@@ -569,13 +573,13 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   // the scalar updates of a whole stage into one lump, and the matrix pipe idles behind it.)
 #define LL_PIN_S(x) asm volatile("" : "+s"(x))
   int w_tile = tile0, w_kt = 0, a_kt = 0;
-  unsigned w_lds = lds_mid, a_lds = lds_mid + SLOT_BYTES;   // M0 value of the stream's next tile
+  unsigned w_lds = lds_mid, a_lds = lds_mid + W_SLOTS * SLOT_BYTES;   // M0 value of the stream's next tile
   const unsigned char* w_base = w_tile_base(tile0);
   const unsigned char* a_base = a_base0;
   set_w_rows(tile0);
   auto advance_w = [&]() {
-    w_lds += 2 * SLOT_BYTES;
-    if (w_lds >= lds_wrap) w_lds -= SLOTS * SLOT_BYTES;
+    w_lds += SLOT_BYTES;
+    if (w_lds >= w_lds_wrap) w_lds -= W_SLOTS * SLOT_BYTES;
     w_base += DK * 2;
     if (++w_kt == KT) {   // next vocabulary tile; past the end of the sweep the ring refetches the last one
       w_kt = 0;
@@ -588,8 +592,7 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
     LL_PIN_S(w_base);
   };
   auto advance_a = [&]() {
-    a_lds += 2 * SLOT_BYTES;
-    if (a_lds >= lds_wrap) a_lds -= SLOTS * SLOT_BYTES;
+    a_lds = a_lds_flip - a_lds;
     a_base += DK * 2;
     if (++a_kt == KT) {
       a_kt = 0;
@@ -617,7 +620,7 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   st.init();
   st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
 
-  // prologue: W0 A0 W1 and the first half of A1 in flight; stage 0 landed
+  // prologue: W0 A0 W1 A1 and the first half of W2 in flight; stage 0 landed
   set_lds_dma_base(w_lds);
   LL_DMA_TILE(LL_DMA_W);
   advance_w();
@@ -628,94 +631,101 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   LL_DMA_TILE(LL_DMA_W);
   advance_w();
   set_lds_dma_base(a_lds);
-  LL_DMA_A(0); LL_DMA_A(1); LL_DMA_A(2); LL_DMA_A(3);
-  __builtin_amdgcn_s_waitcnt(waitcnt_imm(LOADS_PER_TILE + 4, 15));   // W0 and A0 landed
+  LL_DMA_TILE(LL_DMA_A);
+  advance_a();
+  set_lds_dma_base(w_lds);
+  LL_DMA_W(0); LL_DMA_W(1); LL_DMA_W(2); LL_DMA_W(3);
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE + 4, 15));   // W0 and A0 landed
   __syncthreads();
-  bf16x8 fa0[2], fw0[8], fa1[2], fw1[8];
+  bf16x8 fa[4][2], fw0[8], fw1[8];   // A: one pair per k-slice of the stage; W: two sets of one k-slice
 #pragma unroll
-  for (int j = 0; j < 2; ++j) fa0[j] = *reinterpret_cast<const bf16x8*>(smem + SLOT_BYTES + a_wave_off + j * 32 * (DK * 2) + f_off[0]);
+  for (int s = 0; s < 3; ++s)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      fa[s][j] = *reinterpret_cast<const bf16x8*>(smem + W_SLOTS * SLOT_BYTES + a_wave_off + j * 32 * (DK * 2) + f_off[s]);
 #pragma unroll
   for (int i = 0; i < 8; ++i) fw0[i] = *reinterpret_cast<const bf16x8*>(smem + i * 32 * (DK * 2) + f_off[0]);
 
-  // MFMAs of one k-slice from fragment set (fw, fa), with the LDS reads of another slice into
-  // (nw, na) from LDS offsets (tW, tA) slipped in behind the first eight MFMAs, so that the last
-  // read has half a slice to land before the next slice needs it.  HOOK(I) is what else goes
-  // behind the second MFMA of pair I: a load-to-LDS or a piece of the streams' bookkeeping.  The
-  // fences pin that order: no gap between two MFMAs holds more than a handful of instructions.
+  // MFMAs of one k-slice from W fragments fw and the A pair fas, with the LDS reads of another
+  // k-slice's W fragments into nw from LDS offset tW slipped in behind the first eight MFMAs, so
+  // that the last read has half a slice to land before the next slice needs it.  RHOOK(I) is the
+  // A fragment read that goes behind the first MFMA of pair I, HOOK(I) what else goes behind the
+  // second: a load-to-LDS or a piece of the streams' bookkeeping.  The fences pin that order: no
+  // gap between two MFMAs holds more than a handful of instructions.
 #define LL_LDS_FRAG(ptr) (*reinterpret_cast<const bf16x8*>(ptr))
-#define LL_PAIR(I, fw, fa, nw, na, tW, tA, off, HOOK)                                               \
-  acc[I][0] = LL_MFMA(fw[I], fa[0], acc[I][0]);                                                     \
-  if (I == 0) {                                                                                     \
-    na[0] = LL_LDS_FRAG(smem + tA + (off));                                                                \
-    na[1] = LL_LDS_FRAG(smem + tA + 32 * (DK * 2) + (off));                                                \
-  }                                                                                                 \
-  if (I < 4) nw[(2 * I) & 7] = LL_LDS_FRAG(smem + tW + (2 * I) * 32 * (DK * 2) + (off));                         \
+#define LL_PAIR(I, fw, fas, nw, tW, off, RHOOK, HOOK)                                               \
+  acc[I][0] = LL_MFMA(fw[I], fas[0], acc[I][0]);                                                    \
+  RHOOK(I);                                                                                         \
+  if (I < 4) nw[(2 * I) & 7] = LL_LDS_FRAG(smem + tW + (2 * I) * 32 * (DK * 2) + (off));            \
   LL_SCHED_FENCE();                                                                                 \
-  acc[I][1] = LL_MFMA(fw[I], fa[1], acc[I][1]);                                                     \
-  if (I < 4) nw[(2 * I + 1) & 7] = LL_LDS_FRAG(smem + tW + (2 * I + 1) * 32 * (DK * 2) + (off));                 \
+  acc[I][1] = LL_MFMA(fw[I], fas[1], acc[I][1]);                                                    \
+  if (I < 4) nw[(2 * I + 1) & 7] = LL_LDS_FRAG(smem + tW + (2 * I + 1) * 32 * (DK * 2) + (off));    \
   HOOK(I);                                                                                          \
   LL_SCHED_FENCE();
-#define LL_SLICE(fw, fa, nw, na, tW, tA, off, HOOK)                                                 \
+#define LL_SLICE(fw, fas, nw, tW, off, RHOOK, HOOK)                                                 \
   LL_SCHED_FENCE();                                                                                 \
-  LL_PAIR(0, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
-  LL_PAIR(1, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
-  LL_PAIR(2, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
-  LL_PAIR(3, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
-  LL_PAIR(4, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
-  LL_PAIR(5, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
-  LL_PAIR(6, fw, fa, nw, na, tW, tA, off, HOOK)                                                     \
-  LL_PAIR(7, fw, fa, nw, na, tW, tA, off, HOOK)
+  LL_PAIR(0, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
+  LL_PAIR(1, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
+  LL_PAIR(2, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
+  LL_PAIR(3, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
+  LL_PAIR(4, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
+  LL_PAIR(5, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
+  LL_PAIR(6, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
+  LL_PAIR(7, fw, fas, nw, tW, off, RHOOK, HOOK)
 
-  // Load schedule of stage g.  The barrier before slice 3 frees the slots of W(g) and A(g); A(g+2)
-  // takes the first (half of it in slice 3, half in slice 0 of the next stage) and W(g+3) the
-  // second (slices 0 to 2 of the next stage), so that no slice sends more than six loads and the
-  // load pipe never sees a burst.  In stage g that reads: slice 0 finishes A(g+1) and starts
-  // W(g+2), slices 1 and 2 finish W(g+2), slice 3 starts A(g+2).  All of A(g+1) is sent before any
-  // of W(g+2), so "all but the last 8 loads have landed" at the barrier covers stage g+1.
+#define LL_RHOOK_NONE(I) (void)0
+#define LL_RHOOK_S0(I)                                                                 \
+  if (I == 0) {                                                                        \
+    fa[3][0] = LL_LDS_FRAG(smem + cA + f_off[3]);                                      \
+    fa[3][1] = LL_LDS_FRAG(smem + cA + 32 * (DK * 2) + f_off[3]);                      \
+  }
+#define LL_RHOOK_S3(I)                                                                 \
+  if (I < 3) {                                                                         \
+    fa[I & 3][0] = LL_LDS_FRAG(smem + nA + f_off[I & 3]);                              \
+    fa[I & 3][1] = LL_LDS_FRAG(smem + nA + 32 * (DK * 2) + f_off[I & 3]);              \
+  }
 #define LL_HOOK_S0(I)                                \
-  if (I == 0) {                                      \
-    set_lds_dma_base(a_lds);                         \
-    LL_DMA_A(4);                                     \
-  }                                                  \
-  if (I == 1) LL_DMA_A(5);                           \
-  if (I == 2) LL_DMA_A(6);                           \
-  if (I == 3) LL_DMA_A(7);                           \
-  if (I == 4) {                                      \
-    advance_a();                                     \
-    set_lds_dma_base(w_lds);                         \
-  }                                                  \
-  if (I == 5) LL_DMA_W(0);                           \
-  if (I == 6) LL_DMA_W(1);                           \
-  if (I == 7) LL_DMA_W(2)
+  if (I == 0) set_lds_dma_base(w_lds);               \
+  if (I == 3) LL_DMA_W(4);                           \
+  if (I == 4) LL_DMA_W(5);                           \
+  if (I == 5) LL_DMA_W(6);                           \
+  if (I == 6) LL_DMA_W(7);                           \
+  if (I == 7) advance_w()
+  // (the A fragments of k-slice 3 were read at the head of slice 0, and LDS reads return in
+  // order: once the first MFMA of slice 1 has its W fragments, A(g)'s slot is the wavefront's own)
 #define LL_HOOK_S1(I)                                \
-  if (I == 4) LL_DMA_W(3);                           \
-  if (I == 5) LL_DMA_W(4);                           \
-  if (I == 6) LL_DMA_W(5)
-#define LL_HOOK_S2(I)                                \
-  if (I == 4) LL_DMA_W(6);                           \
-  if (I == 5) LL_DMA_W(7);                           \
-  if (I == 6) advance_w()
-#define LL_HOOK_S3(I)                                \
   if (I == 3) set_lds_dma_base(a_lds);               \
   if (I == 4) LL_DMA_A(0);                           \
+  if (I == 5) LL_DMA_A(1);                           \
+  if (I == 6) LL_DMA_A(2);                           \
+  if (I == 7) LL_DMA_A(3)
+#define LL_HOOK_S2(I)                                \
+  if (I == 2) LL_DMA_A(4);                           \
+  if (I == 3) LL_DMA_A(5);                           \
+  if (I == 4) LL_DMA_A(6);                           \
+  if (I == 5) LL_DMA_A(7);                           \
+  if (I == 6) advance_a()
+#define LL_HOOK_S3(I)                                \
+  if (I == 3) set_lds_dma_base(w_lds);               \
+  if (I == 4) LL_DMA_W(0);                           \
   if (I == 5) {                                      \
-    LL_DMA_A(1);                                     \
+    LL_DMA_W(1);                                     \
     cW = nW;                                         \
-    cA = nA;                                         \
-    nW = nW + 2 * SLOT_BYTES >= RING ? nW + 2 * SLOT_BYTES - RING : nW + 2 * SLOT_BYTES;               \
+    nW = nW + SLOT_BYTES >= W_SLOTS * SLOT_BYTES ? 0 : nW + SLOT_BYTES;   \
     LL_PIN_S(nW);                                    \
   }                                                  \
   if (I == 6) {                                      \
-    LL_DMA_A(2);                                     \
-    nA = nA + 2 * SLOT_BYTES >= RING + a_wave_off ? nA + 2 * SLOT_BYTES - RING : nA + 2 * SLOT_BYTES;  \
-    LL_PIN_S(nA);                                    \
+    LL_DMA_W(2);                                     \
+    const int t_ = cA;                               \
+    cA = nA;                                         \
+    nA = t_;                                         \
   }                                                  \
-  if (I == 7) LL_DMA_A(3)
+  if (I == 7) LL_DMA_W(3)
 
   // Consumer state: LDS byte offsets of the W and A tiles of this stage and of the next (the A
   // offsets include the wavefront's own 64 rows).
-  constexpr int RING = SLOTS * SLOT_BYTES;
-  int cW = 0, cA = SLOT_BYTES + a_wave_off, nW = 2 * SLOT_BYTES, nA = 3 * SLOT_BYTES + a_wave_off;
+  int cW = 0, nW = SLOT_BYTES;
+  int cA = W_SLOTS * SLOT_BYTES + a_wave_off, nA = (W_SLOTS + 1) * SLOT_BYTES + a_wave_off;
   for (int tile = tile0; tile < tile1; ++tile) {
     f32x16 acc[8][2];
 #pragma unroll
@@ -726,13 +736,13 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     for (int kt = 0; kt < KT; ++kt) {
-      LL_SLICE(fw0, fa0, fw1, fa1, cW, cA, f_off[1], LL_HOOK_S0)
-      LL_SLICE(fw1, fa1, fw0, fa0, cW, cA, f_off[2], LL_HOOK_S1)
-      LL_SLICE(fw0, fa0, fw1, fa1, cW, cA, f_off[3], LL_HOOK_S2)
-      // stage g+1 landed (only the W tile just sent may still be out); all my reads of stage g done
-      __builtin_amdgcn_s_waitcnt(waitcnt_imm(LOADS_PER_TILE, 0));
+      LL_SLICE(fw0, fa[0], fw1, cW, f_off[1], LL_RHOOK_S0, LL_HOOK_S0)
+      LL_SLICE(fw1, fa[1], fw0, cW, f_off[2], LL_RHOOK_NONE, LL_HOOK_S1)
+      LL_SLICE(fw0, fa[2], fw1, cW, f_off[3], LL_RHOOK_NONE, LL_HOOK_S2)
+      // stage g+1 landed (W(g+2) and A(g+2) may still be out); all my reads of W(g) are done
+      __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE, 0));
       __syncthreads();
-      LL_SLICE(fw1, fa1, fw0, fa0, nW, nA, f_off[0], LL_HOOK_S3)
+      LL_SLICE(fw1, fa[3], fw0, nW, f_off[0], LL_RHOOK_S3, LL_HOOK_S3)
     }
     epilogue_tile<KR, false>(acc, st, tile * BM, V, nullptr);
   }
@@ -741,6 +751,9 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
 #undef LL_LDS_FRAG
 #undef LL_DMA_TILE
 #undef LL_HOOK_S3
+#undef LL_RHOOK_S3
+#undef LL_RHOOK_S0
+#undef LL_RHOOK_NONE
 #undef LL_PIN_S
 #undef LL_HOOK_S2
 #undef LL_HOOK_S1
