@@ -156,18 +156,19 @@ struct RowState {
   }
   __device__ __forceinline__ float tau() const { return lv[KR - 1]; }
   // Branch-free sorted insert: slot j takes its upper neighbour if the candidate goes above that
-  // neighbour, the candidate if it goes exactly here, and keeps its entry otherwise.
+  // neighbour, the candidate if it goes exactly here, and keeps its entry otherwise.  For the
+  // logits that is the median of (upper neighbour, own entry, candidate): one instruction.
   __device__ __forceinline__ void insert(float z, int id) {
     bool above = z > lv[KR - 1];              // candidate ranks above the entry of slot j
 #pragma unroll
     for (int j = KR - 1; j >= 1; --j) {
       const bool above_up = z > lv[j - 1];
-      lv[j] = above_up ? lv[j - 1] : (above ? z : lv[j]);
       li[j] = above_up ? li[j - 1] : (above ? id : li[j]);
+      lv[j] = __builtin_amdgcn_fmed3f(lv[j - 1], lv[j], z);
       above = above_up;
     }
-    lv[0] = above ? z : lv[0];
     li[0] = above ? id : li[0];
+    lv[0] = fmaxf(lv[0], z);
   }
 };
 
@@ -266,9 +267,25 @@ __device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowSta
   // KR-th best: mark the candidates against that threshold, then insert them in id order.
   if (__builtin_amdgcn_ballot_w64(gmax > st.tau()) != 0) {
     const float tau0 = st.tau();
+    // bit o of mask: x[o] > tau0.  Two instructions per entry: the comparison, then the mask
+    // doubled plus the comparison's result as carry-in (entries taken from 31 down to 0).  Four
+    // entries at a time, comparisons first: a VALU result in an SGPR must not be read by the
+    // next two VALU instructions on this hardware.
     unsigned mask = 0;
 #pragma unroll
-    for (int o = 0; o < 32; ++o) mask |= (x[o] > tau0 ? 1u : 0u) << o;
+    for (int o = 28; o >= 0; o -= 4) {
+      unsigned long long c0, c1, c2, c3;
+      asm("v_cmp_gt_f32_e64 %1, %5, %9\n\t"
+          "v_cmp_gt_f32_e64 %2, %6, %9\n\t"
+          "v_cmp_gt_f32_e64 %3, %7, %9\n\t"
+          "v_cmp_gt_f32_e64 %4, %8, %9\n\t"
+          "v_addc_co_u32_e64 %0, %1, %0, %0, %1\n\t"
+          "v_addc_co_u32_e64 %0, %2, %0, %0, %2\n\t"
+          "v_addc_co_u32_e64 %0, %3, %0, %0, %3\n\t"
+          "v_addc_co_u32_e64 %0, %4, %0, %0, %4"
+          : "+v"(mask), "=&s"(c0), "=&s"(c1), "=&s"(c2), "=&s"(c3)
+          : "v"(x[o + 3]), "v"(x[o + 2]), "v"(x[o + 1]), "v"(x[o]), "v"(tau0));
+    }
     if (partial) mask &= (g0 + 32 <= V) ? 0xffffffffu : (g0 >= V ? 0u : (1u << (V - g0)) - 1u);
     while (mask != 0) {
       const int o = __builtin_ctz(mask);
