@@ -137,6 +137,38 @@ int ll_steer_inject(const ll_shape* shape, const void* hidden, const void* gamma
                     const float* v, float alpha, void* out_hidden, void* stream);
 
 /*
+ * Steering sweep: the lens read-out of Eq. 3 (paper Sec. 3.4) for several steering strengths in
+ * ONE pass over W_U.  With a[r, :] the normalised row as in ll_project and u = W_U v (fp32),
+ *
+ *   z_alpha[r, id] = sum_j a[r, j] * W_U[id, j] + alpha * u[id]      ( = W_U (a[r, :] + alpha v) )
+ *
+ * and for every alpha of the list and every row the call returns the most likely token, its
+ * probability, the target token's log-probability and the entropy of softmax(z_alpha[r, :]):
+ * the dose-response curve of Sec. 5 for the cost of one projection instead of one per alpha.
+ * Unlike ll_steer_inject followed by ll_project, the steered row a + alpha v is never rounded to
+ * bf16: the shift alpha * u is added to the fp32 logits.
+ *
+ *   shape, hidden, gamma (NULL = rows already normalised), W_U, eps: as ll_project
+ *   v            fp32 [d], device: the steering direction (e.g. from ll_steer_vector)
+ *   alphas       fp32 [n_alpha], HOST memory, read during the call; 1 <= n_alpha <= LL_SWEEP_MAX
+ *   target_ids   int32 [N] or NULL (then out_target_logp may be NULL and is not written)
+ *   out_top1_ids [n_alpha, N] int32   arg max of z_alpha (smallest id on exact ties)
+ *   out_top1_p   [n_alpha, N] fp32    its full-softmax probability
+ *   out_target_logp [n_alpha, N] fp32 NaN where the target id is outside [0, V)
+ *   out_entropy  [n_alpha, N] fp32    nats
+ * Requirements beyond ll_project's: d a multiple of 64 (LL_EINVAL otherwise).  Workspace:
+ * ll_steer_sweep_workspace_bytes(shape, n_alpha).  Same error, ownership, stream and N == 0
+ * conventions as ll_project.
+ */
+#define LL_SWEEP_MAX 9
+size_t ll_steer_sweep_workspace_bytes(const ll_shape* shape, int n_alpha);
+int ll_steer_sweep(const ll_shape* shape, void* workspace, size_t workspace_bytes,
+                   const void* hidden, const void* gamma, const void* W_U, float eps,
+                   const float* v, const float* alphas, int n_alpha, const int32_t* target_ids,
+                   int32_t* out_top1_ids, float* out_top1_p, float* out_target_logp, float* out_entropy,
+                   void* stream);
+
+/*
  * Chooses the projection kernel for later ll_project calls of this process (not thread safe):
  *   0  automatic (default)
  *   1  register-staged kernel: the RMSNorm scaling is applied inside the A-tile load of the GEMM

@@ -60,6 +60,12 @@ def lib() -> ctypes.CDLL:
         L.ll_steer_inject.argtypes = [POINTER(ll_shape), c_void_p, c_void_p, c_float, c_void_p, c_float,
                                       c_void_p, c_void_p]
         L.ll_steer_inject.restype = c_int
+        L.ll_steer_sweep_workspace_bytes.argtypes = [POINTER(ll_shape), c_int]
+        L.ll_steer_sweep_workspace_bytes.restype = c_size_t
+        L.ll_steer_sweep.argtypes = [POINTER(ll_shape), c_void_p, c_size_t, c_void_p, c_void_p, c_void_p, c_float,
+                                     c_void_p, POINTER(c_float), c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                     c_void_p]
+        L.ll_steer_sweep.restype = c_int
         L.ll_set_gemm_path.argtypes = [c_int]
         L.ll_set_gemm_path.restype = c_int
         L.ll_error_string.argtypes = [c_int]
@@ -183,3 +189,47 @@ def ll_steer_inject(hidden, gamma, eps, v, alpha, *, stream=None, out=None):
     if rc != LL_OK:
         raise LLError(rc, "ll_steer_inject")
     return o.reshape(hidden.shape)
+
+
+LL_SWEEP_MAX = 9
+
+
+def ll_steer_sweep_workspace_bytes(N: int, d: int, V: int, n_alpha: int) -> int:
+    return int(lib().ll_steer_sweep_workspace_bytes(ll_shape(N, d, V), n_alpha))
+
+
+def ll_steer_sweep(hidden, gamma, W_U, eps, v, alphas, target_ids=None, *, workspace=None, stream=None):
+    """Lens read-out of the steered rows RMSNorm(hidden) + alpha v for every alpha of the list in one pass over
+    W_U (paper Eq. 3 / Sec. 3.4).  v [d] fp32 on the GPU, alphas a sequence of at most LL_SWEEP_MAX floats.
+
+    Returns (top1_ids [A,N] int32, top1_p [A,N] fp32, target_logp [A,N] fp32 or None, entropy [A,N] fp32).
+    """
+    d = hidden.shape[-1]
+    h2 = hidden.reshape(-1, d)
+    N = h2.shape[0]
+    V = W_U.shape[0]
+    A = len(alphas)
+    _check(h2, torch.bfloat16, "hidden")
+    _check(W_U, torch.bfloat16, "W_U", (V, d))
+    _check(v, torch.float32, "v", (d,))
+    if gamma is not None:
+        _check(gamma, torch.bfloat16, "gamma", (d,))
+    if target_ids is not None:
+        _check(target_ids, torch.int32, "target_ids", (N,))
+    shape = ll_shape(N, d, V)
+    need = int(lib().ll_steer_sweep_workspace_bytes(shape, A))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=hidden.device)
+    dev = hidden.device
+    ids = torch.empty((A, N), dtype=torch.int32, device=dev)
+    p = torch.empty((A, N), dtype=torch.float32, device=dev)
+    logp = torch.empty((A, N), dtype=torch.float32, device=dev) if target_ids is not None else None
+    ent = torch.empty((A, N), dtype=torch.float32, device=dev)
+    al = (c_float * max(A, 1))(*[float(x) for x in alphas])
+    rc = lib().ll_steer_sweep(shape, _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(h2), _ptr(gamma),
+                              _ptr(W_U), float(eps), _ptr(v), al, A, _ptr(target_ids), _ptr(ids), _ptr(p), _ptr(logp),
+                              _ptr(ent), _stream(stream))
+    if rc != LL_OK:
+        raise LLError(rc, "ll_steer_sweep")
+    return ids, p, logp, ent
+

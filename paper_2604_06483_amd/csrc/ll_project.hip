@@ -117,6 +117,8 @@ __global__ __launch_bounds__(256) void ll_norm_panel_kernel(const uint16_t* __re
 // tile; after exchanging the two row tiles between the lane halves (v_permlane32_swap) lane l of
 // wavefront w holds all 256 logits of lens row 64w + l, so the whole epilogue is lane-private.
 // ---------------------------------------------------------------------------------------
+#define LL_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
 struct GemmArgs {
   const uint16_t* A;        // [rows, lda] bf16 (this pass's rows)
   const float* inv_rms;     // [rows] or nullptr (rows already normalised)
@@ -128,6 +130,11 @@ struct GemmArgs {
   uint2* top;               // [rows, splits, k]  (logit bits, id), sorted
   int64_t lda;              // row stride of A in elements
   int rows, d, V, k, splits, tiles, row_blocks;
+  // steering sweep only (Sec. 3.4, Eq. 3 for several alpha in one pass):
+  const float* au;          // [n_alpha, au_stride] fp32: alpha_a * (W_U v)[id], zero padded to whole tiles
+  float4* sweep_stats;      // [rows, splits, n_alpha]  (m, S, T, bits of the arg max id)
+  float* sweep_ztgt;        // [rows, splits]           logit of the target id at alpha = 0
+  int au_stride, n_alpha;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -208,13 +215,11 @@ __device__ __forceinline__ float select32(const float (&x)[32], int o) {
   return cndmask(e[0], e[1], b4);
 }
 
-// Processes vocabulary entries [v0 + 32 I, v0 + 32 I + 32) of the finished tile for the lane's row.
-template <int I, int KR, bool BIAS>
-__device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowState<KR>& st, int v0, int V, bool partial,
-                                               const float* __restrict__ bias) {
-  // x[o]: logit of vocabulary entry v0 + 32 I + o for this lane's row.  The swap hands the lower
-  // lane half the row tile j = 0 and the upper half j = 1, so that lane l owns row 64 w + l.
-  float x[32];
+// x[o]: logit of vocabulary entry v0 + 32 I + o of the finished tile for this lane's row.  The swap
+// hands the lower lane half the row tile j = 0 and the upper half j = 1, so that lane l owns row
+// 64 w + l.
+template <int I>
+__device__ __forceinline__ void load_group(const f32x16 (&acc)[8][2], float (&x)[32]) {
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc_read(acc[I][0][r])),
@@ -223,6 +228,14 @@ __device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowSta
     x[o] = __uint_as_float(sw[0]);
     x[o + 4] = __uint_as_float(sw[1]);
   }
+}
+
+// Processes vocabulary entries [v0 + 32 I, v0 + 32 I + 32) of the finished tile for the lane's row.
+template <int I, int KR, bool BIAS>
+__device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowState<KR>& st, int v0, int V, bool partial,
+                                               const float* __restrict__ bias) {
+  float x[32];
+  load_group<I>(acc, x);
   const int g0 = v0 + 32 * I;
   if (BIAS) {   // one coalesced load of the group's 32 biases, then a broadcast per entry
     const unsigned b = __float_as_uint(bias[min(g0 + (int)(threadIdx.x & 31), V - 1)]);
@@ -322,6 +335,134 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs& p, const RowState
   for (int j = 0; j < KR; ++j)
     if (j < p.k) p.top[o * p.k + j] = make_uint2(__float_as_uint(st.lv[j]), (unsigned)st.li[j]);
 }
+
+// What a GEMM kernel does with a finished tile is a policy: the state of the lane's row, how a
+// tile updates it, and what goes to the workspace at the end of the sweep.
+template <int KR>
+struct TopKEpilogue {   // a5..a7: softmax statistics, k best logits, target logit
+  using State = RowState<KR>;
+  static __device__ __forceinline__ void init(State& st, const GemmArgs& p, int my_row) {
+    st.init();
+    st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
+  }
+  static __device__ __forceinline__ void tile(const f32x16 (&acc)[8][2], State& st, int v0, const GemmArgs& p) {
+    epilogue_tile<KR, false>(acc, st, v0, p.V, nullptr);
+  }
+  static __device__ __forceinline__ void store(const GemmArgs& p, const State& st, int my_row, int split) {
+    epilogue_store(p, st, my_row, split);
+  }
+};
+
+// ---------------------------------------------------------------------------------------
+// Steering sweep (Sec. 3.4): the logits of h' = norm(h) + alpha v are z + alpha u with u = W_U v,
+// so one pass over W_U serves every alpha: per alpha the lane keeps the softmax statistics and the
+// arg max of z + alpha u.  alpha_a u comes as a table of fp32 per vocabulary id, read through the
+// constant address space (wave-uniform addresses: scalar loads, one SGPR operand per add).
+// ---------------------------------------------------------------------------------------
+constexpr int SWEEP_MAX = LL_SWEEP_MAX;
+typedef const float __attribute__((address_space(4)))* const_f32_ptr;
+
+struct SweepState {
+  float m[SWEEP_MAX], s[SWEEP_MAX], t[SWEEP_MAX];
+  int id[SWEEP_MAX];
+  float z_tgt = -INFINITY;
+  int tgt = -1;
+};
+
+template <int I>
+__device__ __forceinline__ void sweep_group(const f32x16 (&acc)[8][2], SweepState& st, int v0, int V, bool partial,
+                                            const GemmArgs& p) {
+  const int g0 = v0 + 32 * I;
+  const int tl = st.tgt - g0;
+  if (__builtin_amdgcn_ballot_w64((unsigned)tl < 32u) != 0) {
+    float x[32];
+    load_group<I>(acc, x);
+#pragma unroll
+    for (int o = 0; o < 32; ++o)
+      if (tl == o) st.z_tgt = x[o];
+  }
+#pragma unroll
+  for (int a = 0; a < SWEEP_MAX; ++a) {
+    if (a < p.n_alpha) {
+      // The group's logits are fetched from the accumulators again for every alpha: keeping
+      // them next to the shifted copy would not fit the register file.
+      const_f32_ptr au = (const_f32_ptr)(uintptr_t)(p.au + (int64_t)a * p.au_stride + g0);
+      float y[32];
+      load_group<I>(acc, y);
+#pragma unroll
+      for (int o = 0; o < 32; ++o) y[o] += au[o];
+      if (partial) {
+#pragma unroll
+        for (int o = 0; o < 32; ++o)
+          if (g0 + o >= V) y[o] = NEG_BIG;
+      }
+      float gmax = y[0];
+#pragma unroll
+      for (int o = 1; o < 32; ++o) gmax = fmaxf(gmax, y[o]);
+      if (__builtin_amdgcn_ballot_w64(gmax > st.m[a]) != 0) {
+        // a new maximum for some lane: ids come in increasing order, so strictly greater is the
+        // tie rule, and within the group the lowest position with that value wins
+        const bool up = gmax > st.m[a];
+        int pos = 0;
+#pragma unroll
+        for (int o = 31; o >= 0; --o) pos = (y[o] == gmax) ? o : pos;
+        const float m_new = fmaxf(st.m[a], gmax);
+        const float sc = __builtin_amdgcn_exp2f((st.m[a] - m_new) * LOG2E);   // first group: exp2(-inf) = 0
+        st.s[a] *= sc;
+        st.t[a] *= sc;
+        st.m[a] = m_new;
+        st.id[a] = up ? g0 + pos : st.id[a];
+      }
+      const float mb = st.m[a] * LOG2E;
+      float s4[4] = {0.f, 0.f, 0.f, 0.f}, t4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int o = 0; o < 32; ++o) {
+        const float e = __builtin_amdgcn_exp2f(fmaf(y[o], LOG2E, -mb));
+        s4[o & 3] += e;
+        t4[o & 3] = fmaf(e, y[o], t4[o & 3]);
+      }
+      st.s[a] += (s4[0] + s4[1]) + (s4[2] + s4[3]);
+      st.t[a] += (t4[0] + t4[1]) + (t4[2] + t4[3]);
+      // One alpha at a time: without a use of the sums right here the compiler postpones the
+      // exponentials of all nine past the last one's maximum and keeps nine shifted copies alive.
+      asm volatile("" : "+v"(st.s[a]), "+v"(st.t[a]));
+    }
+  }
+}
+
+struct SweepEpilogue {
+  using State = SweepState;
+  static __device__ __forceinline__ void init(State& st, const GemmArgs& p, int my_row) {
+#pragma unroll
+    for (int a = 0; a < SWEEP_MAX; ++a) {
+      st.m[a] = -INFINITY;
+      st.s[a] = 0.f;
+      st.t[a] = 0.f;
+      st.id[a] = INT_MAX;
+    }
+    st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
+  }
+  static __device__ __forceinline__ void tile(const f32x16 (&acc)[8][2], State& st, int v0, const GemmArgs& p) {
+    const bool partial = v0 + BM > p.V;
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");   // as in epilogue_tile: let the last MFMA drain
+    sweep_group<0>(acc, st, v0, p.V, partial, p);
+    sweep_group<1>(acc, st, v0, p.V, partial, p);
+    sweep_group<2>(acc, st, v0, p.V, partial, p);
+    sweep_group<3>(acc, st, v0, p.V, partial, p);
+    sweep_group<4>(acc, st, v0, p.V, partial, p);
+    sweep_group<5>(acc, st, v0, p.V, partial, p);
+    sweep_group<6>(acc, st, v0, p.V, partial, p);
+    sweep_group<7>(acc, st, v0, p.V, partial, p);
+  }
+  static __device__ __forceinline__ void store(const GemmArgs& p, const State& st, int my_row, int split) {
+    if (my_row >= p.rows) return;
+    const int64_t o = (int64_t)my_row * p.splits + split;
+    p.sweep_ztgt[o] = st.z_tgt;
+#pragma unroll
+    for (int a = 0; a < SWEEP_MAX; ++a)
+      if (a < p.n_alpha) p.sweep_stats[o * p.n_alpha + a] = make_float4(st.m[a], st.s[a], st.t[a], __int_as_float(st.id[a]));
+  }
+};
 
 // Workgroup ids are dealt round-robin over the 8 XCDs; remap so that one XCD (one L2) gets a
 // compact rectangle of (row blocks) x (all splits) and its CUs share A panels and W tiles.
@@ -504,7 +645,6 @@ constexpr int waitcnt_imm(int vmcnt, int lgkmcnt) { return (vmcnt & 0xF) | ((vmc
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-#define LL_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 #define LL_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
 // One global_load_lds_dwordx4: every lane fetches 16 bytes from base + off + IMM and the
@@ -532,7 +672,7 @@ __device__ __forceinline__ void set_lds_dma_base(unsigned lds_addr) {
 }
 #pragma clang diagnostic pop
 
-template <int KR>
+template <class EPI>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -633,9 +773,8 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   const int a_wave_off = (wave * 64) * (DK * 2);
 
   const int my_row = rb * BN + tid;
-  RowState<KR> st;
-  st.init();
-  st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
+  typename EPI::State st;
+  EPI::init(st, p, my_row);
 
   // prologue: W0 A0 W1 A1 and the first half of W2 in flight; stage 0 landed
   set_lds_dma_base(w_lds);
@@ -761,7 +900,7 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
       __syncthreads();
       LL_SLICE(fw1, fa[3], fw0, nW, f_off[0], LL_RHOOK_S3, LL_HOOK_S3)
     }
-    epilogue_tile<KR, false>(acc, st, tile * BM, V, nullptr);
+    EPI::tile(acc, st, tile * BM, p);
   }
 #undef LL_SLICE
 #undef LL_PAIR
@@ -778,7 +917,108 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
 #undef LL_DMA_A
 #undef LL_DMA_W
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));   // drain the ring before the LDS is given back
-  epilogue_store(p, st, my_row, split);
+  EPI::store(p, st, my_row, split);
+}
+
+__global__ __launch_bounds__(256) void ll_fill_f32_kernel(float* __restrict__ p, int n, float value) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = value;
+}
+
+// ---------------------------------------------------------------------------------------
+// Steering sweep, step 1: u = W_U v (one pass over W_U, HBM-bound: 2 V d bytes), written as the
+// table au[a, id] = alpha_a * u[id] that the sweep epilogue adds to the logits.  One wavefront
+// takes four vocabulary rows at a time so that a chunk of v read from LDS serves four products.
+// ---------------------------------------------------------------------------------------
+struct AlphaList {
+  float a[SWEEP_MAX];
+};
+
+__global__ __launch_bounds__(256) void ll_unembed_direction_kernel(const uint16_t* __restrict__ W, const float* __restrict__ v,
+                                                                   int V, int d, AlphaList alphas, int n_alpha,
+                                                                   float* __restrict__ au, int au_stride) {
+  extern __shared__ __align__(16) float sv[];
+  for (int j = threadIdx.x; j < d; j += blockDim.x) sv[j] = v[j];
+  __syncthreads();
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int n16 = d >> 3;
+  for (int r0 = (blockIdx.x * 4 + wave) * 4; r0 < V; r0 += gridDim.x * 16) {
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const uint4* rows[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rows[i] = reinterpret_cast<const uint4*>(W + (int64_t)min(r0 + i, V - 1) * d);
+    for (int c = lane; c < n16; c += 64) {
+      const float4 v0 = *reinterpret_cast<const float4*>(sv + 8 * c);
+      const float4 v1 = *reinterpret_cast<const float4*>(sv + 8 * c + 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint4 q = rows[i][c];
+        float a = acc[i];
+        a = fmaf(bf16_lo(q.x), v0.x, a);
+        a = fmaf(bf16_hi(q.x), v0.y, a);
+        a = fmaf(bf16_lo(q.y), v0.z, a);
+        a = fmaf(bf16_hi(q.y), v0.w, a);
+        a = fmaf(bf16_lo(q.z), v1.x, a);
+        a = fmaf(bf16_hi(q.z), v1.y, a);
+        a = fmaf(bf16_lo(q.w), v1.z, a);
+        a = fmaf(bf16_hi(q.w), v1.w, a);
+        acc[i] = a;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float u = wave_sum(acc[i]);
+      if (lane == 0 && r0 + i < V) {
+#pragma unroll
+        for (int a = 0; a < SWEEP_MAX; ++a)
+          if (a < n_alpha) au[(int64_t)a * au_stride + r0 + i] = alphas.a[a] * u;
+      }
+    }
+  }
+}
+
+// Steering sweep, step 3: merge the splits of each (row, alpha) and finalise.  One thread per row.
+__global__ __launch_bounds__(256) void ll_sweep_merge_kernel(const float4* __restrict__ stats, const float* __restrict__ ztgt,
+                                                             const float* __restrict__ au, int au_stride, int rows, int splits,
+                                                             int n_alpha, int V, const int32_t* __restrict__ target,
+                                                             int64_t out_stride, int32_t* __restrict__ out_ids,
+                                                             float* __restrict__ out_p, float* __restrict__ out_logp,
+                                                             float* __restrict__ out_entropy) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= rows) return;
+  int t = -1;
+  float zt0 = -INFINITY;
+  if (target != nullptr) {
+    t = target[row];
+    for (int s = 0; s < splits; ++s) zt0 = fmaxf(zt0, ztgt[(int64_t)row * splits + s]);
+  }
+  const bool t_ok = t >= 0 && t < V;
+  for (int a = 0; a < n_alpha; ++a) {
+    const float4* st = stats + ((int64_t)row * splits) * n_alpha + a;
+    float M = -INFINITY;
+    int best = INT_MAX;
+    for (int s = 0; s < splits; ++s) {   // splits hold increasing id ranges: strictly greater keeps the smallest id
+      const float4 q = st[(int64_t)s * n_alpha];
+      if (q.x > M) {
+        M = q.x;
+        best = __float_as_int(q.w);
+      }
+    }
+    float S = 0.f, T = 0.f;
+    for (int s = 0; s < splits; ++s) {
+      const float4 q = st[(int64_t)s * n_alpha];
+      const float sc = __builtin_amdgcn_exp2f((q.x - M) * LOG2E);
+      S += sc * q.y;
+      T += sc * q.z;
+    }
+    const float logS = logf(S);
+    const int64_t o = (int64_t)a * out_stride + row;
+    out_ids[o] = best;
+    out_p[o] = 1.0f / S;                      // exp(M - (M + log S))
+    out_entropy[o] = (M - T / S) + logS;
+    if (target != nullptr)
+      out_logp[o] = t_ok ? ((zt0 + au[(int64_t)a * au_stride + t]) - M) - logS : __builtin_nanf("");
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -919,7 +1159,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   // The top-k lists live in registers: the kernels are built for a few list lengths KR >= k.
   void (*kern)(const GemmArgs);
 #define LL_PICK(KR) \
-  (dma ? ll_lens_gemm_dma_kernel<KR> : (bias ? ll_lens_gemm_kernel<KR, true> : ll_lens_gemm_kernel<KR, false>))
+  (dma ? ll_lens_gemm_dma_kernel<TopKEpilogue<KR>> : (bias ? ll_lens_gemm_kernel<KR, true> : ll_lens_gemm_kernel<KR, false>))
   if (k <= 4)
     kern = LL_PICK(4);
   else if (k <= 12)
@@ -1026,9 +1266,146 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   return finish(LL_OK);
 }
 
+struct SweepPlan {
+  size_t off_au, off_stats, off_ztgt, off_panel, total;
+  int64_t lda;
+  int au_stride;
+};
+
+SweepPlan make_sweep_plan(const ll_shape* s, int n_alpha) {
+  SweepPlan p;
+  size_t off = 0;
+  p.au_stride = (s->V + BM - 1) / BM * BM;
+  p.off_au = off;
+  off = align_up(off + (size_t)n_alpha * p.au_stride * sizeof(float), 256);
+  const size_t rows = (size_t)(s->N < CHUNK_ROWS ? s->N : CHUNK_ROWS);
+  p.off_stats = off;
+  off = align_up(off + rows * MAX_SPLITS * (size_t)n_alpha * sizeof(float4), 256);
+  p.off_ztgt = off;
+  off = align_up(off + rows * MAX_SPLITS * sizeof(float), 256);
+  p.lda = s->d;
+  p.off_panel = off;
+  off = align_up(off + rows * (size_t)p.lda * sizeof(uint16_t), 256);
+  p.total = off;
+  return p;
+}
+
+bool sweep_shape_ok(const ll_shape* s, int n_alpha) {
+  return shape_ok(s, 1) && s->d % DK == 0 && n_alpha >= 1 && n_alpha <= SWEEP_MAX &&
+         (int64_t)BM * s->d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * s->d * 2 < (int64_t)1 << 31;
+}
+
+int sweep_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
+               const void* W_U, float eps, const float* v, const float* alphas, int n_alpha, const int32_t* target_ids,
+               int32_t* out_ids, float* out_p, float* out_logp, float* out_entropy, hipStream_t stream) {
+  if (!sweep_shape_ok(shape, n_alpha)) return LL_EINVAL;
+  if (shape->N == 0) return LL_OK;
+  if (hidden == nullptr || W_U == nullptr || v == nullptr || alphas == nullptr || out_ids == nullptr || out_p == nullptr ||
+      out_entropy == nullptr)
+    return LL_EINVAL;
+  if (target_ids != nullptr && out_logp == nullptr) return LL_EINVAL;
+  if (!(eps >= 0.f)) return LL_EINVAL;
+  if (((uintptr_t)hidden | (uintptr_t)W_U | (uintptr_t)gamma | (uintptr_t)v) & 15) return LL_EINVAL;
+  AlphaList al;
+  for (int a = 0; a < SWEEP_MAX; ++a) {
+    al.a[a] = a < n_alpha ? alphas[a] : 0.f;
+    if (!(al.a[a] == al.a[a]) || al.a[a] - al.a[a] != 0.f) return LL_EINVAL;   // NaN or infinite
+  }
+  const SweepPlan plan = make_sweep_plan(shape, n_alpha);
+  if (workspace == nullptr || workspace_bytes < plan.total || ((uintptr_t)workspace & 255)) return LL_EWORKSPACE;
+
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  float* au = reinterpret_cast<float*>(ws + plan.off_au);
+  float4* stats = reinterpret_cast<float4*>(ws + plan.off_stats);
+  float* ztgt = reinterpret_cast<float*>(ws + plan.off_ztgt);
+  uint16_t* panel = reinterpret_cast<uint16_t*>(ws + plan.off_panel);
+  const int64_t N = shape->N;
+  const int d = shape->d, V = shape->V;
+  const int tiles = (V + BM - 1) / BM;
+#define LL_CHECK_S(expr)                           \
+  do {                                             \
+    hipError_t e__ = (expr);                       \
+    if (e__ != hipSuccess) return hip_failed(e__); \
+  } while (0)
+
+  // the padding of the table (ids V .. au_stride) is read by the last tile and masked afterwards:
+  // any finite value will do, zero it once
+  if (plan.au_stride > V) {
+    for (int a = 0; a < n_alpha; ++a)
+      hipLaunchKernelGGL(ll_fill_f32_kernel, dim3(1), dim3(256), 0, stream, au + (size_t)a * plan.au_stride + V,
+                         plan.au_stride - V, 0.f);
+    LL_CHECK_S(hipGetLastError());
+  }
+  hipLaunchKernelGGL(ll_unembed_direction_kernel, dim3(NUM_CU * 4), dim3(256), (size_t)d * sizeof(float), stream,
+                     static_cast<const uint16_t*>(W_U), v, V, d, al, n_alpha, au, plan.au_stride);
+  LL_CHECK_S(hipGetLastError());
+  auto kern = ll_lens_gemm_dma_kernel<SweepEpilogue>;
+  const size_t lds = (size_t)SLOTS * SLOT_BYTES;
+  LL_CHECK_S(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+
+  for (int64_t r0 = 0; r0 < N; r0 += CHUNK_ROWS) {
+    const int rows = (int)((N - r0 < CHUNK_ROWS) ? (N - r0) : CHUNK_ROWS);
+    const uint16_t* h_rows = static_cast<const uint16_t*>(hidden) + r0 * d;
+    if (gamma != nullptr) {
+      const dim3 grid((unsigned)((rows + 3) / 4));
+      const uint16_t* g = static_cast<const uint16_t*>(gamma);
+      if (d <= 64 * 8 * 4)
+        hipLaunchKernelGGL(ll_norm_panel_kernel<4>, grid, dim3(256), 0, stream, h_rows, g, panel, rows, d, plan.lda, eps);
+      else if (d <= 64 * 8 * 16)
+        hipLaunchKernelGGL(ll_norm_panel_kernel<16>, grid, dim3(256), 0, stream, h_rows, g, panel, rows, d, plan.lda, eps);
+      else
+        hipLaunchKernelGGL(ll_norm_panel_kernel<0>, grid, dim3(256), 0, stream, h_rows, g, panel, rows, d, plan.lda, eps);
+      LL_CHECK_S(hipGetLastError());
+    }
+    const int row_blocks = (rows + BN - 1) / BN;
+    int splits = NUM_CU / row_blocks;
+    if (splits > MAX_SPLITS) splits = MAX_SPLITS;
+    if (splits > tiles) splits = tiles;
+    if (splits < 1) splits = 1;
+    GemmArgs a = {};
+    a.A = gamma != nullptr ? panel : h_rows;
+    a.lda = plan.lda;
+    a.W = static_cast<const uint16_t*>(W_U);
+    a.target = target_ids ? target_ids + r0 : nullptr;
+    a.rows = rows;
+    a.d = d;
+    a.V = V;
+    a.k = 1;
+    a.splits = splits;
+    a.tiles = tiles;
+    a.row_blocks = row_blocks;
+    a.au = au;
+    a.au_stride = plan.au_stride;
+    a.n_alpha = n_alpha;
+    a.sweep_stats = stats;
+    a.sweep_ztgt = ztgt;
+    const int grid = (row_blocks * splits + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHREADS), lds, stream, a);
+    LL_CHECK_S(hipGetLastError());
+    hipLaunchKernelGGL(ll_sweep_merge_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, (const float4*)stats,
+                       (const float*)ztgt, (const float*)au, plan.au_stride, rows, splits, n_alpha, V, a.target, N,
+                       out_ids + r0, out_p + r0, out_logp ? out_logp + r0 : nullptr, out_entropy + r0);
+    LL_CHECK_S(hipGetLastError());
+  }
+#undef LL_CHECK_S
+  return LL_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+size_t ll_steer_sweep_workspace_bytes(const ll_shape* shape, int n_alpha) {
+  if (!sweep_shape_ok(shape, n_alpha)) return 0;
+  return make_sweep_plan(shape, n_alpha).total;
+}
+
+int ll_steer_sweep(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
+                   const void* W_U, float eps, const float* v, const float* alphas, int n_alpha, const int32_t* target_ids,
+                   int32_t* out_top1_ids, float* out_top1_p, float* out_target_logp, float* out_entropy, void* stream) {
+  return sweep_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, eps, v, alphas, n_alpha, target_ids, out_top1_ids,
+                    out_top1_p, out_target_logp, out_entropy, static_cast<hipStream_t>(stream));
+}
 
 int ll_set_gemm_path(int path) {
   if (path < 0 || path > 2) return LL_EINVAL;

@@ -133,6 +133,33 @@ def test_steer_calls_reject_bad_arguments():
     assert L.ll_steer_inject(LL.ll_shape(0, 64, 0), None, None, 1e-5, None, 1.0, None, None) == LL.LL_OK
 
 
+def test_steer_sweep_rejects_bad_arguments_before_any_device_work():
+    L = LL.lib()
+    f = _fake()
+    al = (ctypes.c_float * 9)(*range(-4, 5))
+    s = LL.ll_shape(16, 64, 300)
+    need = LL.ll_steer_sweep_workspace_bytes(16, 64, 300, 9)
+    assert need > 0 and need % 256 == 0
+    assert LL.ll_steer_sweep_workspace_bytes(16, 72, 300, 9) == 0        # d not a multiple of 64
+    assert LL.ll_steer_sweep_workspace_bytes(16, 64, 300, 0) == 0
+    assert LL.ll_steer_sweep_workspace_bytes(16, 64, 300, LL.LL_SWEEP_MAX + 1) == 0
+    # the table of alpha * (W_U v) is part of the workspace: more alphas, more bytes
+    assert LL.ll_steer_sweep_workspace_bytes(16, 64, 300, 9) > LL.ll_steer_sweep_workspace_bytes(16, 64, 300, 1)
+    call = lambda **kw: L.ll_steer_sweep(*[{**dict(shape=s, ws=_fake(4096 * 256), wsb=1 << 30, h=f, g=f, w=f, eps=1e-5, v=f,
+                                                   al=al, n=9, t=f, ids=f, p=f, lp=f, e=f, st=None), **kw}[k]
+                                           for k in ("shape", "ws", "wsb", "h", "g", "w", "eps", "v", "al", "n", "t", "ids",
+                                                     "p", "lp", "e", "st")])
+    for bad in (dict(h=None), dict(w=None), dict(v=None), dict(al=None), dict(ids=None), dict(p=None), dict(e=None),
+                dict(lp=None), dict(n=0), dict(n=10), dict(eps=-1.0), dict(shape=LL.ll_shape(16, 72, 300)),
+                dict(v=_fake((1 << 20) + 4))):
+        assert call(**bad) == LL.LL_EINVAL, bad
+    nan = (ctypes.c_float * 9)(*([0.0] * 8 + [float("nan")]))
+    assert call(al=nan) == LL.LL_EINVAL
+    assert call(ws=None) == LL.LL_EWORKSPACE
+    assert call(wsb=1024) == LL.LL_EWORKSPACE
+    assert call(shape=LL.ll_shape(0, 64, 300), h=None, w=None, ws=None, wsb=0) == LL.LL_OK
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     h = torch.zeros(4, 64, dtype=torch.bfloat16)

@@ -327,9 +327,43 @@ def pin_steer_inject(O):
     assert np.all(np.diff(np.array(lp), axis=0) > 0)
 
 
+def pin_steer_sweep(O):
+    """Several steering strengths at once: brute force on the steered rows, alpha = 0, and a direction along one channel."""
+    h, g, W, t = rand_case(77, 3, 8, 13)
+    rng = np.random.default_rng(5)
+    v = rng.standard_normal(8).astype(np.float32)
+    alphas = [-2.0, 0.0, 0.5, 3.0]
+    got = O.steer_sweep(h, g, W, 1e-5, v, alphas, t)
+    assert got["top1_ids"].shape == (4, 3)
+    hf, gf, Wf = bits_to_float(h), bits_to_float(g), bits_to_float(W)
+    for ai, al in enumerate(alphas):
+        for r in range(3):
+            ms = math.fsum(x * x for x in hf[r]) / 8
+            a = [BF.round_to_bf16(gf[j] * hf[r][j] / math.sqrt(ms + 1e-5)) for j in range(8)]
+            steered = [a[j] + al * float(v[j]) for j in range(8)]
+            want = BF.project_row(steered, None, [list(w) for w in Wf], 1e-5, 1, int(t[r]))
+            assert got["top1_ids"][ai, r] == want["ids"][0]
+            assert abs(got["top1_p"][ai, r] - want["p"][0]) < 1e-12
+            assert abs(got["entropy"][ai, r] - want["entropy"]) < 1e-12
+            assert abs(got["target_logp"][ai, r] - want["target_logp"]) < 1e-12
+    # alpha = 0 is the plain projection
+    base = O.lens_project(h, g, W, 1e-5, 1, t)
+    assert np.array_equal(got["top1_ids"][1], base["topk_ids"][:, 0])
+    np.testing.assert_allclose(got["entropy"][1], base["entropy"], rtol=1e-13)
+    np.testing.assert_allclose(got["target_logp"][1], base["target_logp"], rtol=1e-13)
+    # along channel j the shift of logit id is alpha * W[id, j]: a large alpha picks the largest / smallest entry
+    e = np.zeros(8, np.float32); e[3] = 1.0
+    far = O.steer_sweep(h, g, W, 1e-5, e, [1e4, -1e4], None)
+    assert np.all(far["top1_ids"][0] == int(np.argmax(Wf[:, 3]))) and np.all(far["top1_ids"][1] == int(np.argmin(Wf[:, 3])))
+    # rows that are already normalised are used as they are
+    a_bits = O.f64_to_bf16_bits(O.rmsnorm(h, g, 1e-5))
+    again = O.steer_sweep(a_bits, None, W, 1e-5, v, alphas, t)
+    np.testing.assert_allclose(again["entropy"], got["entropy"], rtol=1e-13)
+
+
 PINS = [pin_bf16_widen, pin_bf16_round, pin_brute_force, pin_bias, pin_invariants, pin_one_hot, pin_zero_row,
         pin_eps_and_gamma, pin_scale_invariance, pin_library_routines, pin_permutation,
-        pin_synthetic_entropy_band, pin_topk_renormalised, pin_steer_vector, pin_steer_inject]
+        pin_synthetic_entropy_band, pin_topk_renormalised, pin_steer_vector, pin_steer_inject, pin_steer_sweep]
 
 
 @pytest.mark.parametrize("pin", PINS, ids=lambda f: f.__name__)
@@ -450,6 +484,27 @@ def _inject_variant(kind):
     return f
 
 
+def _sweep_variant(kind):
+    def f(hidden_bits, gamma_bits, w_bits, eps, v, alphas, target_ids=None, round_a=True):
+        if kind == "minus":
+            return _real["steer_sweep"](hidden_bits, gamma_bits, w_bits, eps, v, [-x for x in alphas], target_ids, round_a)
+        if kind == "rounds_steered_rows":   # what inject + project does, not what the sweep is defined as
+            outs = []
+            for al in alphas:
+                if gamma_bits is None:
+                    a = _real["bf16_bits_to_f64"](hidden_bits) + al * np.asarray(v, np.float64)[None, :]
+                    bits = _real["f64_to_bf16_bits"](a)
+                else:
+                    a = _real["rmsnorm"](hidden_bits, gamma_bits, eps, round_a=True) + al * np.asarray(v, np.float64)[None, :]
+                    bits = _real["f64_to_bf16_bits"](a)
+                outs.append(_real["lens_project"](bits, None, w_bits, eps, 1, target_ids))
+            return {"top1_ids": np.stack([o["topk_ids"][:, 0] for o in outs]), "top1_p": np.stack([o["topk_p"][:, 0] for o in outs]),
+                    "target_logp": np.stack([o["target_logp"] for o in outs]), "entropy": np.stack([o["entropy"] for o in outs])}
+        if kind == "unnormalised_rows":     # steering added to the raw hidden state
+            return _real["steer_sweep"](hidden_bits, None, w_bits, eps, v, alphas, target_ids, round_a)
+    return f
+
+
 MUTANTS = {
     "rmsnorm_no_eps": dict(rmsnorm=_rmsnorm_variant("no_eps")),
     "rmsnorm_eps_outside_sqrt": dict(rmsnorm=_rmsnorm_variant("eps_outside")),
@@ -470,6 +525,9 @@ MUTANTS = {
     "steer_normalise_rows_first": dict(steer_vector=_steer_variant("normalise_rows_first")),
     "inject_pre_norm": dict(steer_inject=_inject_variant("pre_norm")),
     "inject_minus": dict(steer_inject=_inject_variant("minus")),
+    "sweep_minus": dict(steer_sweep=_sweep_variant("minus")),
+    "sweep_rounds_steered_rows": dict(steer_sweep=_sweep_variant("rounds_steered_rows")),
+    "sweep_unnormalised_rows": dict(steer_sweep=_sweep_variant("unnormalised_rows")),
 }
 
 
