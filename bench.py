@@ -199,6 +199,23 @@ def main():
         "steer_vector_large_GBs": 2.0 * 2 * nb * d / (t_vec * 1e-3) / 1e9, "steer_vector_large_rows": 2 * nb,
         "steer_inject_all_rows_GBs": 4.0 * N * d / (t_inj * 1e-3) / 1e9,
     })
+    # Dose-response sweep (outside the timed region): the middle layer's rows read out for nine alphas, once as
+    # one ll_steer_sweep pass over W_U and once as nine ll_steer_inject + ll_project(gamma=None, k=1) pairs.
+    if d % 64 == 0:
+        alphas = [float(a) for a in range(-4, 5)]
+        tgt_layer = w.target_ids.reshape(cfg.L, cfg.T)[l_star].contiguous()
+        sww = torch.empty(LL.ll_steer_sweep_workspace_bytes(cfg.T, d, V, len(alphas)), dtype=torch.uint8, device=dev)
+        t_sweep = timed_ms(lambda: LL.ll_steer_sweep(layer, w.gamma, w.W_U, cfg.eps, v, alphas, tgt_layer, workspace=sww,
+                                                     stream=stream))
+
+        def nine_pairs():
+            for a in alphas:
+                LL.ll_steer_inject(layer, w.gamma, cfg.eps, v, a, out=steered, stream=stream)
+                LL.ll_project(steered, None, w.W_U, cfg.eps, 1, tgt_layer, workspace=ws, stream=stream)
+        t_pairs = timed_ms(nine_pairs)
+        result["steer_sweep"] = {"rows": cfg.T, "n_alpha": len(alphas), "sweep_ms": t_sweep, "inject_project_pairs_ms": t_pairs,
+                                 "speedup": t_pairs / t_sweep}
+        del sww
     if not args.no_cpu_baseline:
         gpu_np = P.to_numpy(out)
         base_info, rep = cpu_baseline(w, gpu_np, args.sample_rows)

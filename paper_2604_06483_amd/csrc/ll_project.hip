@@ -24,7 +24,8 @@ constexpr int BN = 256;          // lens rows per workgroup (MFMA N side)
 constexpr int BK = 64;           // K step of the register-staged kernel
 constexpr int NTHREADS = 256;    // 4 wavefronts, one per SIMD
 constexpr int CHUNK_ROWS = 8192; // lens rows per pass
-constexpr int MAX_SPLITS = 16;   // vocabulary splits per row block
+constexpr int MAX_SPLITS = 64;   // vocabulary splits per row block: one lane of the merging wavefront each
+constexpr int MAX_PARTIALS = 256 * 256;   // rows of a pass x splits never exceeds rows per workgroup x workgroups
 constexpr int NUM_XCD = 8;
 constexpr int NUM_CU = 256;
 constexpr float NEG_BIG = -3.0e38f;   // stands for "no logit" without the NaNs that -inf would breed
@@ -977,112 +978,128 @@ __global__ __launch_bounds__(256) void ll_unembed_direction_kernel(const uint16_
   }
 }
 
-// Steering sweep, step 3: merge the splits of each (row, alpha) and finalise.  One thread per row.
+// Steering sweep, step 3: merge the splits of each (row, alpha) and finalise.  One wavefront per
+// row, lane s = split s.
+__global__ __launch_bounds__(256) void ll_sweep_merge_kernel(const float4* __restrict__ stats, const float* __restrict__ ztgt,
+                                                             const float* __restrict__ au, int au_stride, int rows, int splits,
+                                                             int n_alpha, int V, const int32_t* __restrict__ target,
+                                                             int64_t out_stride, int32_t* __restrict__ out_ids,
+                                                             float* __restrict__ out_p, float* __restrict__ out_logp,
+                                                             float* __restrict__ out_entropy);
+
+// ---------------------------------------------------------------------------------------
+// a8: merge the splits of each row and finalise.  One thread per row.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, kWave));
+  return x;
+}
+__device__ __forceinline__ int wave_min_int(int x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x = min(x, __shfl_xor(x, off, kWave));
+  return x;
+}
+
+// One wavefront per row, lane s = split s (splits <= 64).
+__global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict__ stats, const uint2* __restrict__ top,
+                                                       int rows, int splits, int k, int V, int topk_softmax,
+                                                       const int32_t* __restrict__ target, int32_t* __restrict__ out_ids,
+                                                       float* __restrict__ out_p, float* __restrict__ out_logp,
+                                                       float* __restrict__ out_entropy) {
+  const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const bool live = lane < splits;
+  float4 q = make_float4(-INFINITY, 0.f, 0.f, -INFINITY);
+  if (live) q = stats[(int64_t)row * splits + lane];
+  const float M = wave_max(q.x);
+  const float sc = live ? __builtin_amdgcn_exp2f((q.x - M) * LOG2E) : 0.f;
+  const float S = wave_sum(sc * q.y);
+  const float T = wave_sum(sc * q.z);
+  const float zt = wave_max(q.w);
+  const float logS = logf(S);
+  if (lane == 0) {
+    out_entropy[row] = (M - T / S) + logS;
+    if (target != nullptr) {
+      const int t = target[row];
+      out_logp[row] = (t >= 0 && t < V) ? (zt - M) - logS : __builtin_nanf("");
+    }
+  }
+  // k-way merge of the per-split sorted lists (descending logit, ascending id): every lane holds the
+  // head of its list; the wavefront's best head goes out and that lane moves on.
+  const uint2* tl = top + ((int64_t)row * splits + lane) * k;
+  int head = 0;
+  float z = -INFINITY;
+  int id = INT_MAX;
+  if (live) {
+    const uint2 e = tl[0];
+    z = __uint_as_float(e.x);
+    id = (int)e.y;
+  }
+  float z0 = 0.f, sk = 0.f;   // top-k-only softmax: the largest selected logit and the sum over the selection
+  float mine = 0.f;           // lane j keeps the j-th selected logit
+  for (int j = 0; j < k; ++j) {
+    const float bz = wave_max(z);
+    const int bi = wave_min_int(z == bz ? id : INT_MAX);
+    if (live && z == bz && id == bi) {   // ids are distinct: exactly one lane
+      ++head;
+      if (head < k) {
+        const uint2 e = tl[head];
+        z = __uint_as_float(e.x);
+        id = (int)e.y;
+      } else {
+        z = -INFINITY;
+        id = INT_MAX;
+      }
+    }
+    if (j == 0) z0 = bz;
+    sk += __builtin_amdgcn_exp2f((bz - z0) * LOG2E);
+    if (lane == j) mine = bz;
+    if (lane == 0) {
+      out_ids[(int64_t)row * k + j] = bi;
+      if (!topk_softmax) out_p[(int64_t)row * k + j] = __builtin_amdgcn_exp2f(((bz - M) - logS) * LOG2E);
+    }
+  }
+  // The paper's own probabilities (Sec. 3.3): a softmax over the k selected logits only.
+  if (topk_softmax && lane < k) out_p[(int64_t)row * k + lane] = __builtin_amdgcn_exp2f((mine - z0) * LOG2E) * (1.0f / sk);
+}
+
 __global__ __launch_bounds__(256) void ll_sweep_merge_kernel(const float4* __restrict__ stats, const float* __restrict__ ztgt,
                                                              const float* __restrict__ au, int au_stride, int rows, int splits,
                                                              int n_alpha, int V, const int32_t* __restrict__ target,
                                                              int64_t out_stride, int32_t* __restrict__ out_ids,
                                                              float* __restrict__ out_p, float* __restrict__ out_logp,
                                                              float* __restrict__ out_entropy) {
-  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const bool live = lane < splits;
   int t = -1;
   float zt0 = -INFINITY;
   if (target != nullptr) {
     t = target[row];
-    for (int s = 0; s < splits; ++s) zt0 = fmaxf(zt0, ztgt[(int64_t)row * splits + s]);
+    zt0 = wave_max(live ? ztgt[(int64_t)row * splits + lane] : -INFINITY);
   }
   const bool t_ok = t >= 0 && t < V;
   for (int a = 0; a < n_alpha; ++a) {
-    const float4* st = stats + ((int64_t)row * splits) * n_alpha + a;
-    float M = -INFINITY;
-    int best = INT_MAX;
-    for (int s = 0; s < splits; ++s) {   // splits hold increasing id ranges: strictly greater keeps the smallest id
-      const float4 q = st[(int64_t)s * n_alpha];
-      if (q.x > M) {
-        M = q.x;
-        best = __float_as_int(q.w);
-      }
+    float4 q = make_float4(-INFINITY, 0.f, 0.f, __int_as_float(INT_MAX));
+    if (live) q = stats[((int64_t)row * splits + lane) * n_alpha + a];
+    const float M = wave_max(q.x);
+    // splits hold increasing id ranges, and within one the smallest id of its maximum is kept
+    const int best = wave_min_int(q.x == M ? __float_as_int(q.w) : INT_MAX);
+    const float sc = live ? __builtin_amdgcn_exp2f((q.x - M) * LOG2E) : 0.f;
+    const float S = wave_sum(sc * q.y);
+    const float T = wave_sum(sc * q.z);
+    if (lane == 0) {
+      const float logS = logf(S);
+      const int64_t o = (int64_t)a * out_stride + row;
+      out_ids[o] = best;
+      out_p[o] = 1.0f / S;                      // exp(M - (M + log S))
+      out_entropy[o] = (M - T / S) + logS;
+      if (target != nullptr)
+        out_logp[o] = t_ok ? ((zt0 + au[(int64_t)a * au_stride + t]) - M) - logS : __builtin_nanf("");
     }
-    float S = 0.f, T = 0.f;
-    for (int s = 0; s < splits; ++s) {
-      const float4 q = st[(int64_t)s * n_alpha];
-      const float sc = __builtin_amdgcn_exp2f((q.x - M) * LOG2E);
-      S += sc * q.y;
-      T += sc * q.z;
-    }
-    const float logS = logf(S);
-    const int64_t o = (int64_t)a * out_stride + row;
-    out_ids[o] = best;
-    out_p[o] = 1.0f / S;                      // exp(M - (M + log S))
-    out_entropy[o] = (M - T / S) + logS;
-    if (target != nullptr)
-      out_logp[o] = t_ok ? ((zt0 + au[(int64_t)a * au_stride + t]) - M) - logS : __builtin_nanf("");
-  }
-}
-
-// ---------------------------------------------------------------------------------------
-// a8: merge the splits of each row and finalise.  One thread per row.
-// ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict__ stats, const uint2* __restrict__ top,
-                                                       int rows, int splits, int k, int V, int topk_softmax,
-                                                       const int32_t* __restrict__ target, int32_t* __restrict__ out_ids,
-                                                       float* __restrict__ out_p, float* __restrict__ out_logp,
-                                                       float* __restrict__ out_entropy) {
-  const int row = blockIdx.x * blockDim.x + threadIdx.x;
-  if (row >= rows) return;
-  const float4* st = stats + (int64_t)row * splits;
-  float M = -INFINITY;
-  for (int s = 0; s < splits; ++s) M = fmaxf(M, st[s].x);
-  float S = 0.f, T = 0.f, zt = -INFINITY;
-  for (int s = 0; s < splits; ++s) {
-    const float4 q = st[s];
-    const float sc = __builtin_amdgcn_exp2f((q.x - M) * LOG2E);
-    S += sc * q.y;
-    T += sc * q.z;
-    zt = fmaxf(zt, q.w);
-  }
-  const float logS = logf(S);
-  out_entropy[row] = (M - T / S) + logS;
-  if (target != nullptr) {
-    const int t = target[row];
-    out_logp[row] = (t >= 0 && t < V) ? (zt - M) - logS : __builtin_nanf("");
-  }
-  // k-way merge of the per-split sorted lists (descending logit, ascending id).
-  int head[MAX_SPLITS];
-#pragma unroll
-  for (int s = 0; s < MAX_SPLITS; ++s) head[s] = 0;
-  const uint2* tl = top + (int64_t)row * splits * k;
-  for (int j = 0; j < k; ++j) {
-    float bz = -INFINITY;
-    int bi = INT_MAX, bs = 0;
-#pragma unroll
-    for (int s = 0; s < MAX_SPLITS; ++s) {
-      if (s < splits && head[s] < k) {
-        const uint2 e = tl[s * k + head[s]];
-        const float z = __uint_as_float(e.x);
-        const int id = (int)e.y;
-        if (z > bz || (z == bz && id < bi)) {
-          bz = z;
-          bi = id;
-          bs = s;
-        }
-      }
-    }
-#pragma unroll
-    for (int s = 0; s < MAX_SPLITS; ++s)
-      if (s == bs) ++head[s];
-    out_ids[(int64_t)row * k + j] = bi;
-    out_p[(int64_t)row * k + j] = topk_softmax ? bz : __builtin_amdgcn_exp2f(((bz - M) - logS) * LOG2E);
-  }
-  if (topk_softmax) {
-    // The paper's own probabilities (Sec. 3.3): a softmax over the k selected logits only.
-    float* zp = out_p + (int64_t)row * k;
-    const float z0 = zp[0];   // the largest
-    float sk = 0.f;
-    for (int j = 0; j < k; ++j) sk += __builtin_amdgcn_exp2f((zp[j] - z0) * LOG2E);
-    const float inv = 1.0f / sk;
-    for (int j = 0; j < k; ++j) zp[j] = __builtin_amdgcn_exp2f((zp[j] - z0) * LOG2E) * inv;
   }
 }
 
@@ -1108,9 +1125,10 @@ Plan make_plan(const ll_shape* s, int k) {
   off = align_up(off + (size_t)s->N * sizeof(float), 256);
   const size_t rows = (size_t)(s->N < CHUNK_ROWS ? s->N : CHUNK_ROWS);
   p.off_stats = off;
-  off = align_up(off + rows * MAX_SPLITS * sizeof(float4), 256);
+  const size_t partials = rows * MAX_SPLITS < (size_t)MAX_PARTIALS ? rows * MAX_SPLITS : (size_t)MAX_PARTIALS;
+  off = align_up(off + partials * sizeof(float4), 256);
   p.off_top = off;
-  off = align_up(off + rows * MAX_SPLITS * (size_t)k * sizeof(uint2), 256);
+  off = align_up(off + partials * (size_t)k * sizeof(uint2), 256);
   p.lda = (s->d + DK - 1) / DK * DK;
   p.off_panel = off;
   off = align_up(off + rows * (size_t)p.lda * sizeof(uint16_t), 256);
@@ -1242,7 +1260,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHREADS), lds, stream, a);
     LL_CHECK_F(hipGetLastError());
     LL_CHECK_F(mark());
-    hipLaunchKernelGGL(ll_merge_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, (const float4*)stats, (const uint2*)top,
+    hipLaunchKernelGGL(ll_merge_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, (const float4*)stats, (const uint2*)top,
                        rows, splits, k, V, (flags & LL_FLAG_TOPK_SOFTMAX) ? 1 : 0, a.target, out_topk_ids + r0 * k,
                        out_topk_p + r0 * k,
                        out_target_logp ? out_target_logp + r0 : nullptr, out_entropy + r0);
@@ -1280,9 +1298,10 @@ SweepPlan make_sweep_plan(const ll_shape* s, int n_alpha) {
   off = align_up(off + (size_t)n_alpha * p.au_stride * sizeof(float), 256);
   const size_t rows = (size_t)(s->N < CHUNK_ROWS ? s->N : CHUNK_ROWS);
   p.off_stats = off;
-  off = align_up(off + rows * MAX_SPLITS * (size_t)n_alpha * sizeof(float4), 256);
+  const size_t partials = rows * MAX_SPLITS < (size_t)MAX_PARTIALS ? rows * MAX_SPLITS : (size_t)MAX_PARTIALS;
+  off = align_up(off + partials * (size_t)n_alpha * sizeof(float4), 256);
   p.off_ztgt = off;
-  off = align_up(off + rows * MAX_SPLITS * sizeof(float), 256);
+  off = align_up(off + partials * sizeof(float), 256);
   p.lda = s->d;
   p.off_panel = off;
   off = align_up(off + rows * (size_t)p.lda * sizeof(uint16_t), 256);
@@ -1382,7 +1401,7 @@ int sweep_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, c
     const int grid = (row_blocks * splits + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHREADS), lds, stream, a);
     LL_CHECK_S(hipGetLastError());
-    hipLaunchKernelGGL(ll_sweep_merge_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, (const float4*)stats,
+    hipLaunchKernelGGL(ll_sweep_merge_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, (const float4*)stats,
                        (const float*)ztgt, (const float*)au, plan.au_stride, rows, splits, n_alpha, V, a.target, N,
                        out_ids + r0, out_p + r0, out_logp ? out_logp + r0 : nullptr, out_entropy + r0);
     LL_CHECK_S(hipGetLastError());
