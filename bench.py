@@ -195,7 +195,18 @@ def main():
     all_out = torch.empty_like(big)
     t_inj = timed_ms(lambda: LL.ll_steer_inject(big, w.gamma, cfg.eps, v, 2.0, out=all_out, stream=stream))
     del all_out
+    # capture store: a prefill-sized append (every token of every layer at once) and one decoding step
+    store = torch.empty((cfg.L, 1, cfg.T, d), dtype=torch.bfloat16, device=dev)
+    t_app = timed_ms(lambda: LL.ll_capture_append(store, w.hidden, 0, stream=stream))
+    one = w.hidden[:, :1].contiguous()
+    t_dec = timed_ms(lambda: LL.ll_capture_append(store, one, cfg.T - 1, stream=stream), reps=20)
+    raw_out = torch.empty_like(big)
+    t_raw = timed_ms(lambda: LL.ll_steer_inject_raw(big, v, 2.0, 1.0, 0.1, out=raw_out, stream=stream))
+    del store, raw_out
     result["aux_hbm"].update({
+        "capture_append_all_tokens_GBs": 4.0 * N * d / (t_app * 1e-3) / 1e9,
+        "capture_append_one_step_us": t_dec * 1e3, "capture_append_one_step_rows": cfg.L,
+        "steer_inject_raw_all_rows_GBs": 4.0 * N * d / (t_raw * 1e-3) / 1e9,
         "steer_vector_large_GBs": 2.0 * 2 * nb * d / (t_vec * 1e-3) / 1e9, "steer_vector_large_rows": 2 * nb,
         "steer_inject_all_rows_GBs": 4.0 * N * d / (t_inj * 1e-3) / 1e9,
     })

@@ -137,6 +137,47 @@ int ll_steer_inject(const ll_shape* shape, const void* hidden, const void* gamma
                     const float* v, float alpha, void* out_hidden, void* stream);
 
 /*
+ * Steering inside the model (paper Sec. 3.4, the unnumbered equation h' = h + alpha v after
+ * Eq. 2, with the "magnitude clipping and layer-specific scaling" of its stability paragraph):
+ * the raw activation of a wrapped layer is shifted along v, without any normalisation,
+ *
+ *   s        = alpha * layer_scale
+ *   beta[r]  = sign(s) * min(|s|, clip_ratio * ||hidden[r, :]||_2)     (clip_ratio > 0)
+ *   beta[r]  = s                                                       (clip_ratio <= 0: no clipping)
+ *   out[r,j] = bf16( hidden[r, j] + beta[r] * v[j] )
+ *
+ * so that with a unit-norm v the shift never exceeds clip_ratio times the row's own length.
+ * The paper names the two safeguards but prints no formula for them: this rule is this
+ * library's reading of it.  Same argument conventions as ll_steer_inject (V ignored; out may be
+ * `hidden` itself); layer_scale and clip_ratio must be finite.
+ */
+int ll_steer_inject_raw(const ll_shape* shape, const void* hidden, const float* v, float alpha,
+                        float layer_scale, float clip_ratio, void* out_hidden, void* stream);
+
+/*
+ * Capture store (paper Sec. 3.1 Stage 2 and the first step of Stage 3; Alg. 1 Phase 1): the
+ * wrapped layers' newest activations are appended to per-(layer, type) trajectories that sit in
+ * HBM in exactly the row order ll_project reads, store[l, c, t, :] = row ((l*C + c)*T + t), so
+ * that "concatenating the slices" costs nothing when decoding starts.
+ *
+ *   store   bf16 [L, C, T, d]   the trajectories (T = token capacity of the run)
+ *   slices  bf16 [L*C, n_tok, d] activations of the n_tok newest tokens for every wrapped layer l
+ *           and activation type c, (l, c)-major: n_tok = 1 in a decoding step (the [1, 1, d]
+ *           slice per layer and type of the paper), n_tok = prompt length for the prefill
+ *   t0      position of the first of these tokens; tokens t0 .. t0 + n_tok - 1 are written
+ * LL_EINVAL if t0 < 0, n_tok < 0 or t0 + n_tok > T, d not a multiple of 8, a null or misaligned
+ * (16 bytes) pointer.  n_tok == 0 is a successful no-op.  The two buffers must not overlap.
+ */
+typedef struct ll_capture_shape {
+  int32_t L;   /* wrapped layers */
+  int32_t C;   /* activation types per layer (attention output, MLP output, block output) */
+  int64_t T;   /* tokens per trajectory */
+  int32_t d;   /* hidden size */
+} ll_capture_shape;
+int ll_capture_append(const ll_capture_shape* shape, void* store, const void* slices, int64_t t0, int64_t n_tok,
+                      void* stream);
+
+/*
  * Steering sweep: the lens read-out of Eq. 3 (paper Sec. 3.4) for several steering strengths in
  * ONE pass over W_U.  With a[r, :] the normalised row as in ll_project and u = W_U v (fp32),
  *

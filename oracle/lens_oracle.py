@@ -49,6 +49,8 @@ __all__ = [
     "steer_vector",
     "steer_inject",
     "steer_sweep",
+    "steer_inject_raw",
+    "concat_trajectories",
 ]
 
 
@@ -229,4 +231,31 @@ def steer_sweep(hidden_bits, gamma_bits, w_bits, eps: float, v, alphas, target_i
             out["target_logp"].append(sm["target_logp"])
         out["entropy"].append(sm["entropy"])
     return {k: np.stack(x) for k, x in out.items() if x}
+
+
+def steer_inject_raw(hidden_bits, v, alpha: float, layer_scale: float = 1.0, clip_ratio: float = 0.0) -> np.ndarray:
+    """h' = h + alpha v inside the model (Sec. 3.4, the equation after Eq. 2), with the two
+    safeguards its stability paragraph names but does not define.  Reading taken here:
+    s = alpha * layer_scale is the strength at this layer, and its magnitude is clipped to
+    clip_ratio * ||h_r||_2 row by row (clip_ratio <= 0: no clipping); the shifted row is
+    rounded to bf16 once.  Returns uint16 bits.  Parity unpinned by the paper (it prints no
+    formula); pinned against the plain equation and the clipping bound.
+    """
+    h = bf16_bits_to_f64(hidden_bits)
+    s = float(alpha) * float(layer_scale)
+    if clip_ratio > 0:
+        cap = float(clip_ratio) * np.sqrt(np.sum(h * h, axis=-1, keepdims=True))
+        beta = np.sign(s) * np.minimum(abs(s), cap)
+    else:
+        beta = np.full(h.shape[:-1] + (1,), s)
+    return f64_to_bf16_bits(h + beta * np.asarray(v, dtype=np.float64)[None, :])
+
+
+def concat_trajectories(step_slices, L: int, C: int) -> np.ndarray:
+    """Stage 3's first step (Sec. 3.1; Alg. 1, Phase 2): the slices recorded during generation,
+    each of shape [L*C, n_i, d] for the n_i newest tokens ((layer, type)-major), concatenated
+    along the token axis into the trajectories H[l, c, :, :] of shape [L, C, T, d].
+    """
+    full = np.concatenate([np.asarray(x) for x in step_slices], axis=1)     # [L*C, T, d]
+    return full.reshape(L, C, full.shape[1], full.shape[2])
 

@@ -33,6 +33,10 @@ class LLError(RuntimeError):
         super().__init__(f"{where}: {msg} ({code})")
 
 
+class ll_capture_shape(Structure):
+    _fields_ = [("L", c_int32), ("C", c_int32), ("T", c_int64), ("d", c_int32)]
+
+
 _PROJECT_ARGS = [POINTER(ll_shape), c_void_p, c_size_t, c_void_p, c_void_p, c_void_p, c_float, c_int,
                  c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
 
@@ -66,6 +70,10 @@ def lib() -> ctypes.CDLL:
                                      c_void_p, POINTER(c_float), c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                      c_void_p]
         L.ll_steer_sweep.restype = c_int
+        L.ll_steer_inject_raw.argtypes = [POINTER(ll_shape), c_void_p, c_void_p, c_float, c_float, c_float, c_void_p, c_void_p]
+        L.ll_steer_inject_raw.restype = c_int
+        L.ll_capture_append.argtypes = [POINTER(ll_capture_shape), c_void_p, c_void_p, c_int64, c_int64, c_void_p]
+        L.ll_capture_append.restype = c_int
         L.ll_set_gemm_path.argtypes = [c_int]
         L.ll_set_gemm_path.restype = c_int
         L.ll_error_string.argtypes = [c_int]
@@ -232,4 +240,35 @@ def ll_steer_sweep(hidden, gamma, W_U, eps, v, alphas, target_ids=None, *, works
     if rc != LL_OK:
         raise LLError(rc, "ll_steer_sweep")
     return ids, p, logp, ent
+
+
+def ll_steer_inject_raw(hidden, v, alpha, layer_scale=1.0, clip_ratio=0.0, *, stream=None, out=None):
+    """bf16(hidden + beta v) with beta = alpha * layer_scale clipped to clip_ratio * ||row||_2 (paper Sec. 3.4,
+    in-model injection with its two safeguards); same shape as hidden."""
+    d = hidden.shape[-1]
+    h2 = hidden.reshape(-1, d)
+    _check(h2, torch.bfloat16, "hidden")
+    _check(v, torch.float32, "v", (d,))
+    o = torch.empty_like(h2) if out is None else out.reshape(-1, d)
+    rc = lib().ll_steer_inject_raw(ll_shape(h2.shape[0], d, 0), _ptr(h2), _ptr(v), float(alpha), float(layer_scale),
+                                   float(clip_ratio), _ptr(o), _stream(stream))
+    if rc != LL_OK:
+        raise LLError(rc, "ll_steer_inject_raw")
+    return o.reshape(hidden.shape)
+
+
+def ll_capture_append(store, slices, t0, *, stream=None):
+    """store [L, C, T, d] bf16, slices [L*C, n_tok, d] bf16: writes tokens t0 .. t0+n_tok-1 of every trajectory
+    (paper Sec. 3.1 Stage 2).  store.reshape(-1, d) is then what ll_project takes."""
+    _check(store, torch.bfloat16, "store")
+    if store.dim() != 4:
+        raise ValueError("store: need [L, C, T, d]")
+    L, C, T, d = store.shape
+    _check(slices, torch.bfloat16, "slices")
+    if slices.dim() != 3 or slices.shape[0] != L * C or slices.shape[2] != d:
+        raise ValueError(f"slices: shape {tuple(slices.shape)}, expected ({L * C}, n_tok, {d})")
+    rc = lib().ll_capture_append(ll_capture_shape(L, C, T, d), _ptr(store), _ptr(slices), int(t0), int(slices.shape[1]),
+                                 _stream(stream))
+    if rc != LL_OK:
+        raise LLError(rc, "ll_capture_append")
 

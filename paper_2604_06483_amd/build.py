@@ -13,7 +13,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["ll_api.hip", "ll_project.hip", "ll_steer.hip"]
+SOURCES = ["ll_api.hip", "ll_project.hip", "ll_steer.hip", "ll_capture.hip"]
 LIB = os.path.join(HERE, "libll.so")
 
 FLAGS = [

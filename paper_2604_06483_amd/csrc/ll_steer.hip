@@ -160,9 +160,96 @@ __global__ __launch_bounds__(256) void ll_steer_inject_kernel(const uint16_t* hi
   }
 }
 
+// In-model injection with the two safeguards (Sec. 3.4, stability paragraph): out = bf16(h + beta v)
+// with beta = s clipped in magnitude to clip_ratio times the row's L2 norm (s = alpha times the
+// layer's scale; clip_ratio <= 0: no clipping).  Same shape as the kernel above, without the norm.
+template <int NITER>
+__global__ __launch_bounds__(256) void ll_steer_inject_raw_kernel(const uint16_t* hidden, const float* __restrict__ v,
+                                                                  uint16_t* out, int64_t n_rows, int d, float s,
+                                                                  float clip_ratio) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n_rows) return;
+  const uint4* src = reinterpret_cast<const uint4*>(hidden + row * (int64_t)d);
+  uint4* dst = reinterpret_cast<uint4*>(out + row * (int64_t)d);
+  const float4* v4 = reinterpret_cast<const float4*>(v);
+  const int n16 = d >> 3;
+
+  float acc0 = 0.f, acc1 = 0.f;
+  uint4 cache[NITER > 0 ? NITER : 1];
+  if (NITER > 0) {
+#pragma unroll
+    for (int it = 0; it < NITER; ++it) {
+      const int c = lane + 64 * it;
+      if (c < n16) {
+        cache[it] = src[c];
+        accum_sq(cache[it], acc0, acc1);
+      }
+    }
+  } else {
+    for (int c = lane; c < n16; c += 64) accum_sq(src[c], acc0, acc1);
+  }
+  float beta = s;
+  if (clip_ratio > 0.f) {
+    const float cap = clip_ratio * sqrtf(wave_sum(acc0 + acc1));
+    beta = copysignf(fminf(fabsf(s), cap), s);
+  }
+
+  auto emit = [&](int c, const uint4 q) {
+    const float4 va = v4[2 * c], vb = v4[2 * c + 1];
+    const uint32_t hw[4] = {q.x, q.y, q.z, q.w};
+    const float vv[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
+    uint32_t ow[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      ow[i] = pack_bf16(fmaf(beta, vv[2 * i], bf16_lo(hw[i])), fmaf(beta, vv[2 * i + 1], bf16_hi(hw[i])));
+    dst[c] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+  };
+  if (NITER > 0) {
+#pragma unroll
+    for (int it = 0; it < NITER; ++it) {
+      const int c = lane + 64 * it;
+      if (c < n16) emit(c, cache[it]);
+    }
+  } else {
+    for (int c = lane; c < n16; c += 64) emit(c, src[c]);
+  }
+}
+
 }  // namespace
 
 extern "C" {
+
+int ll_steer_inject_raw(const ll_shape* shape, const void* hidden, const float* v, float alpha, float layer_scale,
+                        float clip_ratio, void* out_hidden, void* stream_) {
+  if (shape == nullptr || shape->N < 0 || shape->d <= 0 || (shape->d & 7) != 0) return LL_EINVAL;
+  if (shape->N == 0) return LL_OK;
+  if (hidden == nullptr || v == nullptr || out_hidden == nullptr) return LL_EINVAL;
+  const float s = alpha * layer_scale;
+  if (s - s != 0.f || clip_ratio - clip_ratio != 0.f) return LL_EINVAL;   // NaN or infinite
+  if (((uintptr_t)hidden | (uintptr_t)v | (uintptr_t)out_hidden) & 15) return LL_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const int64_t N = shape->N;
+  const int d = shape->d;
+  const unsigned blocks = (unsigned)((N + 3) / 4);
+  const uint16_t* h = static_cast<const uint16_t*>(hidden);
+  uint16_t* o = static_cast<uint16_t*>(out_hidden);
+  const int n16 = d >> 3;
+#define LL_INJECT_RAW(NITER) \
+  hipLaunchKernelGGL(ll_steer_inject_raw_kernel<NITER>, dim3(blocks), dim3(256), 0, stream, h, v, o, N, d, s, clip_ratio)
+  if (n16 <= 64 * 2) {
+    LL_INJECT_RAW(2);
+  } else if (n16 <= 64 * 8) {
+    LL_INJECT_RAW(8);
+  } else if (n16 <= 64 * 16) {
+    LL_INJECT_RAW(16);
+  } else {
+    LL_INJECT_RAW(0);
+  }
+#undef LL_INJECT_RAW
+  LL_HIP_CHECK(hipGetLastError());
+  return LL_OK;
+}
 
 size_t ll_steer_workspace_bytes(int32_t d) {
   if (d <= 0 || (d & 7) != 0) return 0;

@@ -160,6 +160,32 @@ def test_steer_sweep_rejects_bad_arguments_before_any_device_work():
     assert call(shape=LL.ll_shape(0, 64, 300), h=None, w=None, ws=None, wsb=0) == LL.LL_OK
 
 
+def test_inject_raw_and_capture_append_reject_bad_arguments():
+    L = LL.lib()
+    f = _fake()
+    s = LL.ll_shape(4, 64, 0)
+    assert L.ll_steer_inject_raw(None, f, f, 1.0, 1.0, 0.1, f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject_raw(s, None, f, 1.0, 1.0, 0.1, f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject_raw(s, f, None, 1.0, 1.0, 0.1, f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject_raw(s, f, f, 1.0, 1.0, 0.1, None, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject_raw(s, f, f, float("inf"), 1.0, 0.1, f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject_raw(s, f, f, 1.0, 1.0, float("nan"), f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject_raw(LL.ll_shape(4, 60, 0), f, f, 1.0, 1.0, 0.1, f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject_raw(LL.ll_shape(0, 64, 0), None, None, 1.0, 1.0, 0.1, None, None) == LL.LL_OK
+    cs = LL.ll_capture_shape(3, 2, 100, 64)
+    assert L.ll_capture_append(None, f, f, 0, 1, None) == LL.LL_EINVAL
+    assert L.ll_capture_append(cs, None, f, 0, 1, None) == LL.LL_EINVAL
+    assert L.ll_capture_append(cs, f, None, 0, 1, None) == LL.LL_EINVAL
+    assert L.ll_capture_append(cs, f, f, -1, 1, None) == LL.LL_EINVAL
+    assert L.ll_capture_append(cs, f, f, 0, -1, None) == LL.LL_EINVAL
+    assert L.ll_capture_append(cs, f, f, 100, 1, None) == LL.LL_EINVAL          # past the capacity
+    assert L.ll_capture_append(cs, f, f, 60, 41, None) == LL.LL_EINVAL
+    assert L.ll_capture_append(cs, _fake((1 << 20) + 8), f, 0, 1, None) == LL.LL_EINVAL
+    assert L.ll_capture_append(LL.ll_capture_shape(3, 2, 100, 60), f, f, 0, 1, None) == LL.LL_EINVAL
+    assert L.ll_capture_append(LL.ll_capture_shape(0, 2, 100, 64), f, f, 0, 1, None) == LL.LL_EINVAL
+    assert L.ll_capture_append(cs, None, None, 100, 0, None) == LL.LL_OK         # nothing to append
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     h = torch.zeros(4, 64, dtype=torch.bfloat16)

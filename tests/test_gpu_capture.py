@@ -1,0 +1,100 @@
+"""Capture store (paper Sec. 3.1 Stage 2/3) and the in-model injection with its safeguards (Sec. 3.4)
+against the CPU oracle, on a real MI355X."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle.lens_oracle as O
+from paper_2604_06483_amd import binding as LL
+from paper_2604_06483_amd import workloads as WL
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
+
+
+@pytest.mark.parametrize("L,C,T,d,steps", [
+    (4, 3, 40, 512, (17, 1, 1, 1, 5, 1, 14)),      # a prefill, decoding steps, a chunk, up to capacity
+    (1, 1, 9, 8, (1,) * 9),                        # smallest rows
+    (7, 3, 33, 8192, (30, 1, 1, 1)),               # 16 KB rows, prefill-sized append
+    (2, 2, 300, 328, (299, 1)),                    # d not a multiple of 64
+])
+def test_capture_append_builds_the_trajectories(L, C, T, d, steps):
+    say(f"capture_append L={L} C={C} T={T} d={d} steps={steps}")
+    assert sum(steps) == T
+    g = torch.Generator(device=DEV).manual_seed(L * 100 + T)
+    store = torch.full((L, C, T, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    slices, t0 = [], 0
+    for n in steps:
+        s = torch.randn((L * C, n, d), generator=g, device=DEV).to(torch.bfloat16)
+        LL.ll_capture_append(store, s, t0)
+        slices.append(WL.bf16_bits(s))
+        t0 += n
+    torch.cuda.synchronize()
+    want = O.concat_trajectories(slices, L, C)
+    assert np.array_equal(WL.bf16_bits(store), want)            # a copy: bit for bit
+    # an append in the middle touches only its own tokens
+    before = WL.bf16_bits(store).copy()
+    s = torch.randn((L * C, 2, d), generator=g, device=DEV).to(torch.bfloat16)
+    LL.ll_capture_append(store, s, 3)
+    torch.cuda.synchronize()
+    after = WL.bf16_bits(store)
+    before[:, :, 3:5, :] = WL.bf16_bits(s).reshape(L, C, 2, d)
+    assert np.array_equal(after, before)
+    with pytest.raises(LL.LLError):
+        LL.ll_capture_append(store, s, T - 1)                    # would run past the capacity
+
+
+def test_captured_store_is_what_the_projection_reads():
+    """Three activation types captured step by step, then decoded in one call over the whole store."""
+    say("capture -> project")
+    L, C, T, d, V, k = 3, 3, 50, 256, 3000, 5
+    cfg = WL.LensConfig("cap", L=L * C, T=T, d=d, V=V, k=k, n_outliers=4, outlier_scale=20.0)
+    w = WL.make_workload(cfg, DEV, seed=2)
+    traj = w.hidden.reshape(L * C, T, d)
+    store = torch.zeros((L, C, T, d), dtype=torch.bfloat16, device=DEV)
+    LL.ll_capture_append(store, traj[:, :20].contiguous(), 0)
+    for t in range(20, T):
+        LL.ll_capture_append(store, traj[:, t:t + 1].contiguous(), t)
+    got = LL.ll_project(store.reshape(-1, d), w.gamma, w.W_U, cfg.eps, k, w.target_ids)
+    ref = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, k, w.target_ids)
+    torch.cuda.synchronize()
+    for a, b in zip(got, ref):
+        assert torch.equal(a, b)
+    rows = np.arange(0, L * C * T, 7)
+    want = P.oracle_rows(WL.bf16_bits(store.reshape(-1, d))[rows], WL.bf16_bits(w.gamma), WL.bf16_bits(w.W_U), cfg.eps, k,
+                         w.target_ids.cpu().numpy()[rows])
+    P.compare(P.take(P.to_numpy(got), rows), want, k, label="captured store")
+
+
+@pytest.mark.parametrize("N,d", [(300, 4096), (7, 328), (130, 8192), (33, 64), (20, 9000)])
+def test_steer_inject_raw(N, d):
+    say(f"steer_inject_raw N={N} d={d}")
+    g = torch.Generator(device=DEV).manual_seed(N + d)
+    h = (3 * torch.randn((N, d), generator=g, device=DEV)).to(torch.bfloat16)
+    h[0] = 0                                                     # a zero row: the cap is zero
+    v = torch.randn((d,), generator=g, device=DEV)
+    v = v / v.norm()
+    hb = WL.bf16_bits(h)
+    for alpha, scale, clip in ((2.5, 1.0, 0.0), (-4.0, 0.5, 0.0), (50.0, 1.0, 0.1), (-50.0, 2.0, 0.05), (0.3, 1.0, 0.5)):
+        out = LL.ll_steer_inject_raw(h, v, alpha, scale, clip)
+        torch.cuda.synchronize()
+        got = O.bf16_bits_to_f64(WL.bf16_bits(out))
+        want = O.bf16_bits_to_f64(O.steer_inject_raw(hb, v.cpu().numpy(), alpha, scale, clip))
+        # fp32 norm and fma before the one bf16 rounding: at most one bf16 step where the sum sits on a rounding boundary
+        hf = O.bf16_bits_to_f64(hb)
+        bound = np.abs(want) * 2.0 ** -7 + (np.abs(hf) + abs(alpha * scale) * np.abs(v.cpu().numpy())[None, :]) * 2.0 ** -20
+        assert np.all(np.abs(got - want) <= bound), f"alpha={alpha} clip={clip}"
+        assert (got != want).mean() < 5e-3
+        if clip > 0:
+            assert np.array_equal(got[0], np.zeros(d))           # nothing may be added to a zero row
+    h2 = h.clone()
+    LL.ll_steer_inject_raw(h2, v, 2.5, 1.0, 0.2, out=h2)          # in place
+    torch.cuda.synchronize()
+    assert torch.equal(h2, LL.ll_steer_inject_raw(h, v, 2.5, 1.0, 0.2))

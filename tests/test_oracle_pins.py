@@ -361,9 +361,55 @@ def pin_steer_sweep(O):
     np.testing.assert_allclose(again["entropy"], got["entropy"], rtol=1e-13)
 
 
+def pin_steer_inject_raw(O):
+    """In-model injection: the plain equation without clipping, a hand-computed clipped row, and the clipping bound."""
+    rng = np.random.default_rng(11)
+    h = to_bits(rng.standard_normal((5, 16)) * 3)
+    hf = bits_to_float(h)
+    v = rng.standard_normal(16); v /= np.linalg.norm(v)
+    # no clipping: h + alpha * scale * v, one rounding (brute force with the pure-Python rounding)
+    got = bits_to_float(O.steer_inject_raw(h, v, 1.5, 2.0, 0.0))
+    for r in range(5):
+        want = [BF.round_to_bf16(float(hf[r, j]) + 3.0 * float(v[j])) for j in range(16)]
+        assert list(got[r]) == want
+    # hand-made row of length 5, unit direction along a free channel: alpha 10 clipped to 0.2 * 5 = 1
+    row = np.zeros((1, 8)); row[0, 0], row[0, 1] = 3.0, 4.0
+    e = np.zeros(8); e[2] = 1.0
+    out = bits_to_float(O.steer_inject_raw(to_bits(row), e, 10.0, 1.0, 0.2))
+    assert list(out[0]) == [3.0, 4.0, 1.0, 0, 0, 0, 0, 0]
+    out = bits_to_float(O.steer_inject_raw(to_bits(row), e, -10.0, 1.0, 0.2))
+    assert out[0, 2] == -1.0                                   # the sign survives the clipping
+    out = bits_to_float(O.steer_inject_raw(to_bits(row), e, 0.5, 1.0, 0.2))
+    assert out[0, 2] == 0.5                                    # below the cap: untouched
+    out = bits_to_float(O.steer_inject_raw(to_bits(row), e, 0.5, 4.0, 0.2))
+    assert out[0, 2] == 1.0                                    # the layer's scale counts before the clipping
+    # the shift never exceeds clip_ratio * ||h|| (plus the output rounding), and reaches it when clipped
+    big = bits_to_float(O.steer_inject_raw(h, v, 100.0, 1.0, 0.25))
+    shift = np.linalg.norm(big - hf, axis=1)
+    cap = 0.25 * np.linalg.norm(hf, axis=1)
+    assert np.all(shift <= cap * 1.01) and np.all(shift >= cap * 0.99)
+
+
+def pin_concat_trajectories(O):
+    """Appending slices step by step gives the same store as writing every token where it belongs."""
+    rng = np.random.default_rng(3)
+    L, C, d = 3, 2, 8
+    steps = [rng.integers(0, 65536, size=(L * C, n, d)).astype(np.uint16) for n in (5, 1, 1, 3, 1)]
+    H = O.concat_trajectories(steps, L, C)
+    assert H.shape == (L, C, 11, d) and H.dtype == np.uint16
+    t = 0
+    for sl in steps:
+        for i in range(sl.shape[1]):
+            for l in range(L):
+                for c in range(C):
+                    assert np.array_equal(H[l, c, t], sl[l * C + c, i])
+            t += 1
+
+
 PINS = [pin_bf16_widen, pin_bf16_round, pin_brute_force, pin_bias, pin_invariants, pin_one_hot, pin_zero_row,
         pin_eps_and_gamma, pin_scale_invariance, pin_library_routines, pin_permutation,
-        pin_synthetic_entropy_band, pin_topk_renormalised, pin_steer_vector, pin_steer_inject, pin_steer_sweep]
+        pin_synthetic_entropy_band, pin_topk_renormalised, pin_steer_vector, pin_steer_inject, pin_steer_sweep, pin_steer_inject_raw,
+        pin_concat_trajectories]
 
 
 @pytest.mark.parametrize("pin", PINS, ids=lambda f: f.__name__)
@@ -505,6 +551,31 @@ def _sweep_variant(kind):
     return f
 
 
+def _inject_raw_variant(kind):
+    def f(hidden_bits, v, alpha, layer_scale=1.0, clip_ratio=0.0):
+        h = _real["bf16_bits_to_f64"](hidden_bits)
+        s = alpha * layer_scale
+        if kind == "scale_after_clip":
+            cap = clip_ratio * np.sqrt(np.sum(h * h, -1, keepdims=True)) if clip_ratio > 0 else np.inf
+            beta = np.sign(alpha) * np.minimum(abs(alpha), cap) * layer_scale
+        elif kind == "clip_to_rms":
+            cap = clip_ratio * np.sqrt(np.mean(h * h, -1, keepdims=True)) if clip_ratio > 0 else np.inf
+            beta = np.sign(s) * np.minimum(abs(s), cap)
+        elif kind == "sign_lost":
+            cap = clip_ratio * np.sqrt(np.sum(h * h, -1, keepdims=True)) if clip_ratio > 0 else np.inf
+            beta = np.minimum(abs(s), cap) * np.ones((h.shape[0], 1))
+        return _real["f64_to_bf16_bits"](h + beta * np.asarray(v, np.float64)[None, :])
+    return f
+
+
+def _concat_variant(kind):
+    def f(step_slices, L, C):
+        full = np.concatenate([np.asarray(x) for x in step_slices], axis=1)
+        if kind == "type_major":      # (type, layer) instead of (layer, type)
+            return full.reshape(C, L, full.shape[1], full.shape[2]).transpose(1, 0, 2, 3)
+    return f
+
+
 MUTANTS = {
     "rmsnorm_no_eps": dict(rmsnorm=_rmsnorm_variant("no_eps")),
     "rmsnorm_eps_outside_sqrt": dict(rmsnorm=_rmsnorm_variant("eps_outside")),
@@ -528,6 +599,10 @@ MUTANTS = {
     "sweep_minus": dict(steer_sweep=_sweep_variant("minus")),
     "sweep_rounds_steered_rows": dict(steer_sweep=_sweep_variant("rounds_steered_rows")),
     "sweep_unnormalised_rows": dict(steer_sweep=_sweep_variant("unnormalised_rows")),
+    "inject_raw_scale_after_clip": dict(steer_inject_raw=_inject_raw_variant("scale_after_clip")),
+    "inject_raw_clip_to_rms": dict(steer_inject_raw=_inject_raw_variant("clip_to_rms")),
+    "inject_raw_sign_lost": dict(steer_inject_raw=_inject_raw_variant("sign_lost")),
+    "concat_type_major": dict(concat_trajectories=_concat_variant("type_major")),
 }
 
 
