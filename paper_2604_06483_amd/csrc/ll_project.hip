@@ -204,16 +204,22 @@ __device__ __forceinline__ float select32(const float (&x)[32], int o) {
   const unsigned long long b2 = __builtin_amdgcn_ballot_w64((o & 4) != 0);
   const unsigned long long b3 = __builtin_amdgcn_ballot_w64((o & 8) != 0);
   const unsigned long long b4 = __builtin_amdgcn_ballot_w64((o & 16) != 0);
+  // All five masks exist from here on, and two wait states have passed: on this hardware a VALU
+  // result in an SGPR must not be read by a VALU instruction issued within the next two, and the
+  // compiler, which would otherwise slide each comparison down to its first use, does not see
+  // inside the select instructions below.
+  unsigned long long m0_ = b0, m1_ = b1, m2_ = b2, m3_ = b3, m4_ = b4;
+  asm volatile("s_nop 1" : "+s"(m0_), "+s"(m1_), "+s"(m2_), "+s"(m3_), "+s"(m4_));
   float a[16], b[8], c[4], e[2];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) a[i] = cndmask(x[2 * i], x[2 * i + 1], b0);
+  for (int i = 0; i < 16; ++i) a[i] = cndmask(x[2 * i], x[2 * i + 1], m0_);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) b[i] = cndmask(a[2 * i], a[2 * i + 1], b1);
+  for (int i = 0; i < 8; ++i) b[i] = cndmask(a[2 * i], a[2 * i + 1], m1_);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) c[i] = cndmask(b[2 * i], b[2 * i + 1], b2);
+  for (int i = 0; i < 4; ++i) c[i] = cndmask(b[2 * i], b[2 * i + 1], m2_);
 #pragma unroll
-  for (int i = 0; i < 2; ++i) e[i] = cndmask(c[2 * i], c[2 * i + 1], b3);
-  return cndmask(e[0], e[1], b4);
+  for (int i = 0; i < 2; ++i) e[i] = cndmask(c[2 * i], c[2 * i + 1], m3_);
+  return cndmask(e[0], e[1], m4_);
 }
 
 // x[o]: logit of vocabulary entry v0 + 32 I + o of the finished tile for this lane's row.  The swap

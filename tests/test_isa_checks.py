@@ -68,3 +68,29 @@ def test_projection_kernels_fit_one_wave_per_simd_without_scratch(asm):
     assert len(dma) == 5
     for name, v in dma.items():
         assert v["vgpr"] <= 512 and v["scratch"] == 0 and v["vspill"] == 0, (name, v)
+
+
+def test_no_valu_reads_an_sgpr_a_valu_wrote_within_two_instructions(asm):
+    """gfx950 needs two wait states between a VALU instruction that writes an SGPR (a comparison,
+    a carry-out) and a VALU instruction that reads it.  The compiler keeps that distance for its
+    own instructions but does not look inside inline asm: check the hand-written selects and
+    add-with-carry of the top-k epilogue."""
+    bodies = {**kernel_bodies(asm, "ll_lens_gemm_dma_kernel"), **kernel_bodies(asm, "ll_lens_gemm_kernel")}
+    assert bodies
+    checked = 0
+    for name, ins in bodies.items():
+        ins = [l.split(";")[0].strip() for l in ins]
+        ins = [l for l in ins if l]
+        for i, l in enumerate(ins):
+            m = re.fullmatch(r"v_cndmask_b32 v\d+, v\d+, v\d+, (s\[\d+:\d+\])", l) or \
+                re.fullmatch(r"v_addc_co_u32_e64 v\d+, s\[\d+:\d+\], v\d+, v\d+, (s\[\d+:\d+\])", l)
+            if not m:
+                continue
+            checked += 1
+            sreg = m.group(1)
+            for prev in ins[max(0, i - 2):i]:
+                ops = prev.split(None, 1)
+                if len(ops) == 2 and ops[0].startswith("v_"):
+                    dests = ops[1].split(",")[:2]            # destination, and carry-out where there is one
+                    assert all(sreg != dd.strip() for dd in dests), (name, prev, l)
+    assert checked > 1000
