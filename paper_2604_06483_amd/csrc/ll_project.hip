@@ -18,6 +18,7 @@ using namespace ll;
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int BM = 256;          // vocabulary rows per tile (MFMA M side)
 constexpr int BN = 256;          // lens rows per workgroup (MFMA N side)
@@ -111,12 +112,13 @@ __global__ __launch_bounds__(256) void ll_norm_panel_kernel(const uint16_t* __re
 // a3..a7: the fused kernels.
 //
 // One workgroup owns BN = 256 lens rows and one vocabulary split; it sweeps the split's 256-wide
-// vocabulary tiles.  Per tile the logits Z^T[vocab, row] = W_tile . A^T are accumulated with
-// v_mfma_f32_32x32x16_bf16 (vocabulary on the M side, lens rows on the N side): wavefront w owns
-// lens rows [64w, 64w+64) against all 256 vocabulary rows, i.e. 8 x 2 accumulator tiles of
-// 32 x 32.  In that accumulator layout a lane holds 16 vocabulary entries of ONE lens row per
-// tile; after exchanging the two row tiles between the lane halves (v_permlane32_swap) lane l of
-// wavefront w holds all 256 logits of lens row 64w + l, so the whole epilogue is lane-private.
+// vocabulary tiles.  Per tile the logits Z^T[vocab, row] = W_tile . A^T are accumulated with bf16
+// MFMAs, vocabulary on the M side, lens rows on the N side: wavefront w owns lens rows
+// [64w, 64w+64) against all 256 vocabulary rows (8 x 2 accumulator tiles of 32 x 32 in the
+// register-staged kernel, 16 x 4 tiles of 16 x 16 in the direct-to-LDS kernel).  In the
+// accumulator layouts a lane holds vocabulary entries of ONE lens row per tile; after exchanging
+// the row tiles between lane blocks (v_permlane32_swap, v_permlane16_swap) lane l of wavefront w
+// holds all 256 logits of lens row 64w + l, so the whole epilogue is lane-private.
 // ---------------------------------------------------------------------------------------
 #define LL_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -237,9 +239,35 @@ __device__ __forceinline__ void load_group(const f32x16 (&acc)[8][2], float (&x)
   }
 }
 
+// The same for the accumulators of v_mfma_f32_16x16x32_bf16: 16 x 4 tiles of 16 x 16, where lane l
+// holds, of tile (i, j), vocabulary rows 4 (l/16) + r (r = 0..3) of lens row 16 j + l%16.  Seen as
+// blocks of 16 lanes, register j of lane block g has to go to register g of lane block j: a 4 x 4
+// transpose, done by one round of v_permlane32_swap (blocks 2,3 of one register against blocks
+// 0,1 of another) and one of v_permlane16_swap (odd blocks against even blocks).  Afterwards lane
+// l owns lens row 64 w + l again, and register g holds vocabulary row 16 i + 4 g + r.
+template <int I>
+__device__ __forceinline__ void load_group(const f32x4 (&acc)[16][4], float (&x)[32]) {
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      unsigned R0 = __float_as_uint(acc_read(acc[2 * I + t][0][r])), R1 = __float_as_uint(acc_read(acc[2 * I + t][1][r]));
+      unsigned R2 = __float_as_uint(acc_read(acc[2 * I + t][2][r])), R3 = __float_as_uint(acc_read(acc[2 * I + t][3][r]));
+      auto a = __builtin_amdgcn_permlane32_swap(R0, R2, false, false);
+      auto b = __builtin_amdgcn_permlane32_swap(R1, R3, false, false);
+      auto c = __builtin_amdgcn_permlane16_swap(a[0], b[0], false, false);
+      auto d = __builtin_amdgcn_permlane16_swap(a[1], b[1], false, false);
+      x[16 * t + r] = __uint_as_float(c[0]);
+      x[16 * t + 4 + r] = __uint_as_float(c[1]);
+      x[16 * t + 8 + r] = __uint_as_float(d[0]);
+      x[16 * t + 12 + r] = __uint_as_float(d[1]);
+    }
+  }
+}
+
 // Processes vocabulary entries [v0 + 32 I, v0 + 32 I + 32) of the finished tile for the lane's row.
-template <int I, int KR, bool BIAS>
-__device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowState<KR>& st, int v0, int V, bool partial,
+template <int I, int KR, bool BIAS, class ACC>
+__device__ __forceinline__ void epilogue_group(const ACC& acc, RowState<KR>& st, int v0, int V, bool partial,
                                                const float* __restrict__ bias) {
   float x[32];
   load_group<I>(acc, x);
@@ -315,21 +343,21 @@ __device__ __forceinline__ void epilogue_group(const f32x16 (&acc)[8][2], RowSta
   }
 }
 
-template <int KR, bool BIAS>
-__device__ __forceinline__ void epilogue_tile(const f32x16 (&acc)[8][2], RowState<KR>& st, int v0, int V,
+template <int KR, bool BIAS, class ACC>
+__device__ __forceinline__ void epilogue_tile(const ACC& acc, RowState<KR>& st, int v0, int V,
                                               const float* __restrict__ bias) {
   const bool partial = v0 + BM > V;
   // The accumulators are read below through inline asm, which the compiler's MFMA hazard
   // bookkeeping does not see: let the last MFMA of the tile drain first.
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-  epilogue_group<0, KR, BIAS>(acc, st, v0, V, partial, bias);
-  epilogue_group<1, KR, BIAS>(acc, st, v0, V, partial, bias);
-  epilogue_group<2, KR, BIAS>(acc, st, v0, V, partial, bias);
-  epilogue_group<3, KR, BIAS>(acc, st, v0, V, partial, bias);
-  epilogue_group<4, KR, BIAS>(acc, st, v0, V, partial, bias);
-  epilogue_group<5, KR, BIAS>(acc, st, v0, V, partial, bias);
-  epilogue_group<6, KR, BIAS>(acc, st, v0, V, partial, bias);
-  epilogue_group<7, KR, BIAS>(acc, st, v0, V, partial, bias);
+  epilogue_group<0, KR, BIAS, ACC>(acc, st, v0, V, partial, bias);
+  epilogue_group<1, KR, BIAS, ACC>(acc, st, v0, V, partial, bias);
+  epilogue_group<2, KR, BIAS, ACC>(acc, st, v0, V, partial, bias);
+  epilogue_group<3, KR, BIAS, ACC>(acc, st, v0, V, partial, bias);
+  epilogue_group<4, KR, BIAS, ACC>(acc, st, v0, V, partial, bias);
+  epilogue_group<5, KR, BIAS, ACC>(acc, st, v0, V, partial, bias);
+  epilogue_group<6, KR, BIAS, ACC>(acc, st, v0, V, partial, bias);
+  epilogue_group<7, KR, BIAS, ACC>(acc, st, v0, V, partial, bias);
 }
 
 // Per-(row, split) partial results: (m, S, T, z_target) and the k best (logit bits, id) pairs.
@@ -352,8 +380,9 @@ struct TopKEpilogue {   // a5..a7: softmax statistics, k best logits, target log
     st.init();
     st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
   }
-  static __device__ __forceinline__ void tile(const f32x16 (&acc)[8][2], State& st, int v0, const GemmArgs& p) {
-    epilogue_tile<KR, false>(acc, st, v0, p.V, nullptr);
+  template <class ACC>
+  static __device__ __forceinline__ void tile(const ACC& acc, State& st, int v0, const GemmArgs& p) {
+    epilogue_tile<KR, false, ACC>(acc, st, v0, p.V, nullptr);
   }
   static __device__ __forceinline__ void store(const GemmArgs& p, const State& st, int my_row, int split) {
     epilogue_store(p, st, my_row, split);
@@ -376,8 +405,8 @@ struct SweepState {
   int tgt = -1;
 };
 
-template <int I>
-__device__ __forceinline__ void sweep_group(const f32x16 (&acc)[8][2], SweepState& st, int v0, int V, bool partial,
+template <int I, class ACC>
+__device__ __forceinline__ void sweep_group(const ACC& acc, SweepState& st, int v0, int V, bool partial,
                                             const GemmArgs& p) {
   const int g0 = v0 + 32 * I;
   const int tl = st.tgt - g0;
@@ -449,17 +478,18 @@ struct SweepEpilogue {
     }
     st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
   }
-  static __device__ __forceinline__ void tile(const f32x16 (&acc)[8][2], State& st, int v0, const GemmArgs& p) {
+  template <class ACC>
+  static __device__ __forceinline__ void tile(const ACC& acc, State& st, int v0, const GemmArgs& p) {
     const bool partial = v0 + BM > p.V;
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");   // as in epilogue_tile: let the last MFMA drain
-    sweep_group<0>(acc, st, v0, p.V, partial, p);
-    sweep_group<1>(acc, st, v0, p.V, partial, p);
-    sweep_group<2>(acc, st, v0, p.V, partial, p);
-    sweep_group<3>(acc, st, v0, p.V, partial, p);
-    sweep_group<4>(acc, st, v0, p.V, partial, p);
-    sweep_group<5>(acc, st, v0, p.V, partial, p);
-    sweep_group<6>(acc, st, v0, p.V, partial, p);
-    sweep_group<7>(acc, st, v0, p.V, partial, p);
+    sweep_group<0, ACC>(acc, st, v0, p.V, partial, p);
+    sweep_group<1, ACC>(acc, st, v0, p.V, partial, p);
+    sweep_group<2, ACC>(acc, st, v0, p.V, partial, p);
+    sweep_group<3, ACC>(acc, st, v0, p.V, partial, p);
+    sweep_group<4, ACC>(acc, st, v0, p.V, partial, p);
+    sweep_group<5, ACC>(acc, st, v0, p.V, partial, p);
+    sweep_group<6, ACC>(acc, st, v0, p.V, partial, p);
+    sweep_group<7, ACC>(acc, st, v0, p.V, partial, p);
   }
   static __device__ __forceinline__ void store(const GemmArgs& p, const State& st, int my_row, int split) {
     if (my_row >= p.rows) return;
@@ -602,7 +632,7 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
       }
     }
-    epilogue_tile<KR, BIAS>(acc, st, v0, V, p.bias);
+    epilogue_tile<KR, BIAS, f32x16[8][2]>(acc, st, v0, V, p.bias);
   }
   epilogue_store(p, st, my_row, split);
 }
@@ -617,8 +647,13 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
 // LDS holds five 32 KB slots, each one operand tile [256 rows][128 B]: a ring of three for the
 // W tiles (stage g in slot g % 3) and a ring of two for the A tiles (stage g in slot 3 + g % 2).
 // The 16-byte chunk index is XOR-swizzled with (row/2)%8, which makes the 8 rows x 8 chunks that
-// one load instruction writes (1 KB, lane-linear) and the 32 rows x 1 chunk that a fragment read
+// one load instruction writes (1 KB, lane-linear) and the 16 rows x 4 chunks that a fragment read
 // touches both bank-conflict free.
+//
+// The matrix instruction here is v_mfma_f32_16x16x32_bf16 (vocabulary on the M side as in the
+// other kernel: 16 x 4 accumulator tiles of 16 x 16 per wavefront).  At the same rate it moves
+// half the accumulator bytes per flop of the 32x32x16 form, and on this power-limited chip that
+// is worth 11 % on a bare MFMA loop and 4 % on this kernel.
 //
 // Wavefront w loads rows [64w, 64w+64) of every tile.  Of a W tile it reads all rows, so W slots
 // change hands at a workgroup barrier; of an A tile it reads exactly the rows it loaded itself,
@@ -627,16 +662,17 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
 // stage are read early (32 registers), and both streams get about two stages between sending a
 // load and needing its data, from the same 160 KB.
 //
-// Schedule of stage g, four k-slices of 16 (W fragments alternate between two register sets):
-//   slice 0    : MFMAs of k-slice 0; reads the W fragments of k-slice 1 and the A fragments of
-//                k-slice 3 (the last of the stage: the wavefront's rows of A(g)'s slot are free);
-//                sends the second half of W(g+2);
-//   slices 1, 2: MFMAs; read the W fragments of the next k-slice; send A(g+2), half each;
+// Schedule of stage g, four slices of 32 MFMAs: (K half 0, vocabulary tiles 0-7), (0, 8-15),
+// (1, 0-7), (1, 8-15); W fragments alternate between two register sets of eight:
+//   slice 0    : reads the W fragments of slice 1 and the A fragments of K half 1 (the last of
+//                the stage: the wavefront's rows of A(g)'s slot are free); sends the second half
+//                of W(g+2);
+//   slices 1, 2: read the W fragments of the next slice; send A(g+2), half each;
 //   wait + barrier: all loads but the last 16 (W(g+2), A(g+2)) have landed, so stage g+1 is in
 //                LDS for everyone, and everyone holds its last fragments of W(g): that slot is free;
-//   slice 3    : MFMAs; reads the W fragments of k-slice 0 and the A fragments of k-slices 0 to 2
-//                of stage g+1; sends the first half of W(g+3) into the slot of W(g).
-// Four loads per slice, one behind every second MFMA, keep the load pipe evenly fed and the
+//   slice 3    : reads the W fragments of slice 0 and the A fragments of K half 0 of stage g+1;
+//                sends the first half of W(g+3) into the slot of W(g).
+// Four loads per slice, one behind every eighth MFMA, keep the load pipe evenly fed and the
 // wavefront's issue slots free for the matrix pipe.  The rings are fed unconditionally and run on
 // across vocabulary tiles (the next tile's first stages load under the epilogue); past the last
 // real stage they re-fetch the last tile, never consumed, which keeps the count of loads in
@@ -652,8 +688,6 @@ constexpr int waitcnt_imm(int vmcnt, int lgkmcnt) { return (vmcnt & 0xF) | ((vmc
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-#define LL_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
-
 // One global_load_lds_dwordx4: every lane fetches 16 bytes from base + off + IMM and the
 // wavefront's 1 KB lands lane-linear at LDS byte address M0 + IMM (the instruction's immediate
 // offset moves both addresses).  Written as an instruction rather than through the builtin: the
@@ -661,7 +695,7 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // read wait for ALL loads in flight, which would serialise the ring; here all waits are the
 // explicit s_waitcnt of the main loop.  One instruction per load, with the LDS base set once per
 // tile, matters: a wavefront alone on its SIMD issues one instruction every four cycles or so, and
-// whatever sits between two MFMAs beyond the 32 cycles the first one runs leaves the pipe idle.
+// whatever sits between two MFMAs beyond the 16 cycles the first one runs leaves the pipe idle.
 template <int IMM>
 __device__ __forceinline__ void load_to_lds_16(const unsigned char* base, unsigned off) {
   static_assert(IMM >= -4096 && IMM < 4096, "13-bit signed immediate");
@@ -678,6 +712,11 @@ __device__ __forceinline__ void set_lds_dma_base(unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(lds_addr) : "memory", "m0");
 }
 #pragma clang diagnostic pop
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+  return c;
+}
 
 template <class EPI>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
@@ -769,14 +808,15 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
 #define LL_DMA_A(S) load_to_lds_16<((S) - 4) * 1024>(a_base, a_off[S])
 #define LL_DMA_TILE(DMA) DMA(0); DMA(1); DMA(2); DMA(3); DMA(4); DMA(5); DMA(6); DMA(7)
 
-  // --- MFMA fragment map: lane reads row (lane % 32) of each 32-row group; k-slice s is the
-  // logical 16-byte chunk 2s + lane/32 of the row.
-  const int f_row = lane & 31;
-  const int f_half = lane >> 5;
+  // --- MFMA fragment map (v_mfma_f32_16x16x32_bf16): lane reads row (lane % 16) of each 16-row
+  // group; of the two K = 32 halves of a stage, half hk is the logical 16-byte chunks
+  // 4 hk + lane/16 of the row.
+  const int f_row = lane & 15;
+  const int f_grp = lane >> 4;
   const int f_swz = (f_row >> 1) & 7;
-  int f_off[4];
+  int f_off[2];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) f_off[s] = f_row * (DK * 2) + (((2 * s + f_half) ^ f_swz) * 16);
+  for (int hk = 0; hk < 2; ++hk) f_off[hk] = f_row * (DK * 2) + (((4 * hk + f_grp) ^ f_swz) * 16);
   const int a_wave_off = (wave * 64) * (DK * 2);
 
   const int my_row = rb * BN + tid;
@@ -800,53 +840,57 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   LL_DMA_W(0); LL_DMA_W(1); LL_DMA_W(2); LL_DMA_W(3);
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE + 4, 15));   // W0 and A0 landed
   __syncthreads();
-  bf16x8 fa[4][2], fw0[8], fw1[8];   // A: one pair per k-slice of the stage; W: two sets of one k-slice
+  // A: the four row tiles of both K halves of the stage; W: two sets of eight vocabulary tiles of one half
+  bf16x8 fa[2][4], fw0[8], fw1[8];
 #pragma unroll
-  for (int s = 0; s < 3; ++s)
+  for (int j = 0; j < 4; ++j)
+    fa[0][j] = *reinterpret_cast<const bf16x8*>(smem + W_SLOTS * SLOT_BYTES + a_wave_off + j * 16 * (DK * 2) + f_off[0]);
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      fa[s][j] = *reinterpret_cast<const bf16x8*>(smem + W_SLOTS * SLOT_BYTES + a_wave_off + j * 32 * (DK * 2) + f_off[s]);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) fw0[i] = *reinterpret_cast<const bf16x8*>(smem + i * 32 * (DK * 2) + f_off[0]);
+  for (int i = 0; i < 8; ++i) fw0[i] = *reinterpret_cast<const bf16x8*>(smem + i * 16 * (DK * 2) + f_off[0]);
 
-  // MFMAs of one k-slice from W fragments fw and the A pair fas, with the LDS reads of another
-  // k-slice's W fragments into nw from LDS offset tW slipped in behind the first eight MFMAs, so
-  // that the last read has half a slice to land before the next slice needs it.  RHOOK(I) is the
-  // A fragment read that goes behind the first MFMA of pair I, HOOK(I) what else goes behind the
-  // second: a load-to-LDS or a piece of the streams' bookkeeping.  The fences pin that order: no
-  // gap between two MFMAs holds more than a handful of instructions.
+  // A stage is four slices of 32 MFMAs: (K half 0, vocabulary tiles 0-7), (0, 8-15), (1, 0-7),
+  // (1, 8-15).  One slice: eight vocabulary tiles (fragments fw) against the four row tiles of a
+  // K half (fah), accumulators MB .. MB+7.  An MFMA runs for 16 cycles, so a gap between two of
+  // them holds at most two or three other instructions: behind the first MFMA of a row of four
+  // goes the LDS read of one W fragment of the next slice (into nw, from LDS offset tW),
+  // behind the second an A fragment read (RHOOK), behind the third a load-to-LDS or a piece of
+  // the streams' bookkeeping (HOOK).  The fences pin that order.
 #define LL_LDS_FRAG(ptr) (*reinterpret_cast<const bf16x8*>(ptr))
-#define LL_PAIR(I, fw, fas, nw, tW, off, RHOOK, HOOK)                                               \
-  acc[I][0] = LL_MFMA(fw[I], fas[0], acc[I][0]);                                                    \
-  RHOOK(I);                                                                                         \
-  if (I < 4) nw[(2 * I) & 7] = LL_LDS_FRAG(smem + tW + (2 * I) * 32 * (DK * 2) + (off));            \
-  LL_SCHED_FENCE();                                                                                 \
-  acc[I][1] = LL_MFMA(fw[I], fas[1], acc[I][1]);                                                    \
-  if (I < 4) nw[(2 * I + 1) & 7] = LL_LDS_FRAG(smem + tW + (2 * I + 1) * 32 * (DK * 2) + (off));    \
-  HOOK(I);                                                                                          \
+  // Written as an instruction so that the 64 accumulator tiles stay in AGPRs: given the builtin,
+  // the register allocator keeps some of them in VGPRs and copies them in and out around the MFMA.
+  // (Operands come from LDS reads, whose waits the compiler still places; nothing reads an
+  // accumulator before the epilogue's own drain.)
+#define LL_MFMA16(a, b, c) mfma16(a, b, c)
+#define LL_ROW(I, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                        \
+  acc[MB + I][0] = LL_MFMA16(fw[I], fah[0], acc[MB + I][0]);                                         \
+  nw[I] = LL_LDS_FRAG(smem + tW + (NMB + I) * 16 * (DK * 2) + (off));                                \
+  LL_SCHED_FENCE();                                                                                  \
+  acc[MB + I][1] = LL_MFMA16(fw[I], fah[1], acc[MB + I][1]);                                         \
+  RHOOK(I);                                                                                          \
+  LL_SCHED_FENCE();                                                                                  \
+  acc[MB + I][2] = LL_MFMA16(fw[I], fah[2], acc[MB + I][2]);                                         \
+  HOOK(I);                                                                                           \
+  LL_SCHED_FENCE();                                                                                  \
+  acc[MB + I][3] = LL_MFMA16(fw[I], fah[3], acc[MB + I][3]);                                         \
   LL_SCHED_FENCE();
-#define LL_SLICE(fw, fas, nw, tW, off, RHOOK, HOOK)                                                 \
-  LL_SCHED_FENCE();                                                                                 \
-  LL_PAIR(0, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
-  LL_PAIR(1, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
-  LL_PAIR(2, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
-  LL_PAIR(3, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
-  LL_PAIR(4, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
-  LL_PAIR(5, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
-  LL_PAIR(6, fw, fas, nw, tW, off, RHOOK, HOOK)                                                     \
-  LL_PAIR(7, fw, fas, nw, tW, off, RHOOK, HOOK)
+#define LL_SLICE(MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                         \
+  LL_SCHED_FENCE();                                                                                  \
+  LL_ROW(0, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(1, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(2, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(3, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(4, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(5, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(6, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(7, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)
 
 #define LL_RHOOK_NONE(I) (void)0
-#define LL_RHOOK_S0(I)                                                                 \
-  if (I == 0) {                                                                        \
-    fa[3][0] = LL_LDS_FRAG(smem + cA + f_off[3]);                                      \
-    fa[3][1] = LL_LDS_FRAG(smem + cA + 32 * (DK * 2) + f_off[3]);                      \
-  }
-#define LL_RHOOK_S3(I)                                                                 \
-  if (I < 3) {                                                                         \
-    fa[I & 3][0] = LL_LDS_FRAG(smem + nA + f_off[I & 3]);                              \
-    fa[I & 3][1] = LL_LDS_FRAG(smem + nA + 32 * (DK * 2) + f_off[I & 3]);              \
-  }
+  // slice 0 fetches the A fragments of the stage's second K half (the last of A(g) this wavefront
+  // needs), slice 3 those of the next stage's first half
+#define LL_RHOOK_S0(I) \
+  if (I < 4) fa[1][I & 3] = LL_LDS_FRAG(smem + cA + (I & 3) * 16 * (DK * 2) + f_off[1])
+#define LL_RHOOK_S3(I) \
+  if (I < 4) fa[0][I & 3] = LL_LDS_FRAG(smem + nA + (I & 3) * 16 * (DK * 2) + f_off[0])
 #define LL_HOOK_S0(I)                                \
   if (I == 0) set_lds_dma_base(w_lds);               \
   if (I == 3) LL_DMA_W(4);                           \
@@ -854,8 +898,8 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   if (I == 5) LL_DMA_W(6);                           \
   if (I == 6) LL_DMA_W(7);                           \
   if (I == 7) advance_w()
-  // (the A fragments of k-slice 3 were read at the head of slice 0, and LDS reads return in
-  // order: once the first MFMA of slice 1 has its W fragments, A(g)'s slot is the wavefront's own)
+  // (the last A fragments of the stage were read early in slice 0, and LDS reads return in order:
+  // once slice 1 has its first W fragment, A(g)'s slot is the wavefront's own)
 #define LL_HOOK_S1(I)                                \
   if (I == 3) set_lds_dma_base(a_lds);               \
   if (I == 4) LL_DMA_A(0);                           \
@@ -873,9 +917,8 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   if (I == 4) LL_DMA_W(0);                           \
   if (I == 5) {                                      \
     LL_DMA_W(1);                                     \
-    cW = nW;                                         \
-    nW = nW + SLOT_BYTES >= W_SLOTS * SLOT_BYTES ? 0 : nW + SLOT_BYTES;   \
-    LL_PIN_S(nW);                                    \
+    nnW = nW + SLOT_BYTES >= W_SLOTS * SLOT_BYTES ? 0 : nW + SLOT_BYTES;   \
+    LL_PIN_S(nnW);                                   \
   }                                                  \
   if (I == 6) {                                      \
     LL_DMA_W(2);                                     \
@@ -883,34 +926,39 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
     cA = nA;                                         \
     nA = t_;                                         \
   }                                                  \
-  if (I == 7) LL_DMA_W(3)
+  if (I == 7) {   /* every row of the slice reads a W fragment from nW: move on after the last */ \
+    LL_DMA_W(3);                                     \
+    cW = nW;                                         \
+    nW = nnW;                                        \
+  }
 
   // Consumer state: LDS byte offsets of the W and A tiles of this stage and of the next (the A
   // offsets include the wavefront's own 64 rows).
-  int cW = 0, nW = SLOT_BYTES;
+  int cW = 0, nW = SLOT_BYTES, nnW = 2 * SLOT_BYTES;
   int cA = W_SLOTS * SLOT_BYTES + a_wave_off, nA = (W_SLOTS + 1) * SLOT_BYTES + a_wave_off;
   for (int tile = tile0; tile < tile1; ++tile) {
-    f32x16 acc[8][2];
+    f32x4 acc[16][4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 16; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
     for (int kt = 0; kt < KT; ++kt) {
-      LL_SLICE(fw0, fa[0], fw1, cW, f_off[1], LL_RHOOK_S0, LL_HOOK_S0)
-      LL_SLICE(fw1, fa[1], fw0, cW, f_off[2], LL_RHOOK_NONE, LL_HOOK_S1)
-      LL_SLICE(fw0, fa[2], fw1, cW, f_off[3], LL_RHOOK_NONE, LL_HOOK_S2)
+      LL_SLICE(0, fw0, fa[0], fw1, cW, 8, f_off[0], LL_RHOOK_S0, LL_HOOK_S0)
+      LL_SLICE(8, fw1, fa[0], fw0, cW, 0, f_off[1], LL_RHOOK_NONE, LL_HOOK_S1)
+      LL_SLICE(0, fw0, fa[1], fw1, cW, 8, f_off[1], LL_RHOOK_NONE, LL_HOOK_S2)
       // stage g+1 landed (W(g+2) and A(g+2) may still be out); all my reads of W(g) are done
       __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE, 0));
       __syncthreads();
-      LL_SLICE(fw1, fa[3], fw0, nW, f_off[0], LL_RHOOK_S3, LL_HOOK_S3)
+      LL_SLICE(8, fw1, fa[1], fw0, nW, 0, f_off[0], LL_RHOOK_S3, LL_HOOK_S3)
     }
     EPI::tile(acc, st, tile * BM, p);
   }
 #undef LL_SLICE
-#undef LL_PAIR
+#undef LL_ROW
+#undef LL_MFMA16
 #undef LL_LDS_FRAG
 #undef LL_DMA_TILE
 #undef LL_HOOK_S3
@@ -926,6 +974,7 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));   // drain the ring before the LDS is given back
   EPI::store(p, st, my_row, split);
 }
+
 
 __global__ __launch_bounds__(256) void ll_fill_f32_kernel(float* __restrict__ p, int n, float value) {
   for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = value;
