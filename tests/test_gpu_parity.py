@@ -66,6 +66,11 @@ RAGGED = [
     ("k1-d8",          2,  70,    8,  513,  1, 0),      # smallest d, V = 2 tiles + 1
     ("many-blocks",    5, 300,  192, 2048, 10, 4),      # N=1500: 6 row blocks, 8 tiles
     ("wide-d",         1,  96, 1096,  777, 20, 0),
+    # d a multiple of 64: these reach the direct-to-LDS kernel
+    ("lds-ragged",     3, 171,  256, 3333, 12, 2),      # N=513: 3 row blocks, the last with one row; 14 tiles, last partial
+    ("lds-k32",        2, 150,  320, 5000, 32, 0),      # 5 K stages, longest top-k list
+    ("lds-one-stage",  1, 300,   64, 1500,  5, 0),      # a single K stage per tile
+    ("lds-64-splits",  1,  64,  128, 20000, 20, 0),     # one row block: 64 vocabulary splits of one or two tiles
 ]
 
 
