@@ -214,8 +214,9 @@ int ll_steer_sweep(const ll_shape* shape, void* workspace, size_t workspace_byte
  *   0  automatic (default)
  *   1  register-staged kernel: the RMSNorm scaling is applied inside the A-tile load of the GEMM
  *   2  direct-to-LDS kernel fed from a normalised bf16 panel written once per row pass
- * Both compute the same quantities from the same bf16 operands; results agree bit for bit
- * unless the accumulation order of a logit differs (it does not: same K order).  For tuning
+ * Both compute the same quantities from the same bf16 operands (the normalised row is rounded
+ * to bf16 identically); they use different MFMA shapes, so a logit's fp32 partial sums are
+ * added in a different order and results agree to fp32 accumulation rounding.  For tuning
  * and tests.  Returns LL_EINVAL for any other value.
  */
 int ll_set_gemm_path(int path);
