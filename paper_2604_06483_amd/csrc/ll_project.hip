@@ -167,18 +167,41 @@ struct RowState {
   __device__ __forceinline__ float tau() const { return lv[KR - 1]; }
   // Branch-free sorted insert: slot j takes its upper neighbour if the candidate goes above that
   // neighbour, the candidate if it goes exactly here, and keeps its entry otherwise.  For the
-  // logits that is the median of (upper neighbour, own entry, candidate): one instruction.
+  // logits that is the median of (upper neighbour, own entry, candidate): one instruction.  Four
+  // slots at a time, written as instructions: all comparisons of a block first, into four SGPR
+  // pairs, then the medians, then the id selects.  Left to the compiler every comparison goes
+  // through VCC with two wait states before the select that reads it (a VALU result in an SGPR
+  // must not be read by the next two VALU instructions on this hardware).
   __device__ __forceinline__ void insert(float z, int id) {
-    bool above = z > lv[KR - 1];              // candidate ranks above the entry of slot j
+    static_assert(KR % 4 == 0, "blocks of four");
+    unsigned long long above;   // lanes whose candidate ranks above the entry of the block's top slot
+    asm("v_cmp_gt_f32_e64 %0, %1, %2" : "=s"(above) : "v"(z), "v"(lv[KR - 1]));
 #pragma unroll
-    for (int j = KR - 1; j >= 1; --j) {
-      const bool above_up = z > lv[j - 1];
-      li[j] = above_up ? li[j - 1] : (above ? id : li[j]);
-      lv[j] = __builtin_amdgcn_fmed3f(lv[j - 1], lv[j], z);
-      above = above_up;
+    for (int j = KR - 1; j >= 3; j -= 4) {
+      const float up_v = j >= 4 ? lv[j >= 4 ? j - 4 : 0] : INFINITY;   // nothing ranks above slot 0's upper neighbour
+      const int up_i = li[j >= 4 ? j - 4 : 0];
+      unsigned long long m1, m2, m3, m4;
+      asm("v_cmp_gt_f32_e64 %9, %13, %2\n\t"     // above slot j-1
+          "v_cmp_gt_f32_e64 %10, %13, %3\n\t"    // above slot j-2
+          "v_cmp_gt_f32_e64 %11, %13, %4\n\t"    // above slot j-3
+          "v_cmp_gt_f32_e64 %12, %13, %15\n\t"   // above slot j-4 (the next block's top slot)
+          "v_med3_f32 %1, %2, %1, %13\n\t"       // new logits, top slot first: each reads its still old upper neighbour
+          "v_med3_f32 %2, %3, %2, %13\n\t"
+          "v_med3_f32 %3, %4, %3, %13\n\t"
+          "v_med3_f32 %4, %15, %4, %13\n\t"
+          "v_cndmask_b32_e64 %5, %5, %14, %0\n\t"    // id of slot j: the candidate's if it ranks above the old entry ...
+          "v_cndmask_b32_e64 %5, %5, %6, %9\n\t"     // ... the upper neighbour's if it ranks above that one too
+          "v_cndmask_b32_e64 %6, %6, %14, %9\n\t"
+          "v_cndmask_b32_e64 %6, %6, %7, %10\n\t"
+          "v_cndmask_b32_e64 %7, %7, %14, %10\n\t"
+          "v_cndmask_b32_e64 %7, %7, %8, %11\n\t"
+          "v_cndmask_b32_e64 %8, %8, %14, %11\n\t"
+          "v_cndmask_b32_e64 %8, %8, %16, %12\n\t"
+          "s_mov_b64 %0, %12"
+          : "+s"(above), "+v"(lv[j]), "+v"(lv[j - 1]), "+v"(lv[j - 2]), "+v"(lv[j - 3]), "+v"(li[j]), "+v"(li[j - 1]),
+            "+v"(li[j - 2]), "+v"(li[j - 3]), "=&s"(m1), "=&s"(m2), "=&s"(m3), "=&s"(m4)
+          : "v"(z), "v"(id), "v"(up_v), "v"(up_i));
     }
-    li[0] = above ? id : li[0];
-    lv[0] = fmaxf(lv[0], z);
   }
 };
 
@@ -277,7 +300,8 @@ __device__ __forceinline__ void epilogue_group(const ACC& acc, RowState<KR>& st,
 #pragma unroll
     for (int o = 0; o < 32; ++o) x[o] += __uint_as_float(__builtin_amdgcn_readlane(b, o));
   }
-  if (partial) {
+  if (partial) {   // only the last tile of the vocabulary: a real branch (the empty asm keeps it one)
+    asm volatile("");
 #pragma unroll
     for (int o = 0; o < 32; ++o)
       if (g0 + o >= V) x[o] = NEG_BIG;
@@ -427,7 +451,8 @@ __device__ __forceinline__ void sweep_group(const ACC& acc, SweepState& st, int 
       load_group<I>(acc, y);
 #pragma unroll
       for (int o = 0; o < 32; ++o) y[o] += au[o];
-      if (partial) {
+      if (partial) {   // only the last tile of the vocabulary: a real branch (the empty asm keeps it one)
+        asm volatile("");
 #pragma unroll
         for (int o = 0; o < 32; ++o)
           if (g0 + o >= V) y[o] = NEG_BIG;
