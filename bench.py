@@ -31,15 +31,19 @@ def measured_traffic(config_name):
     import hashlib
     import re
     path = os.path.join(ROOT, "profiles", f"ll_lens_gemm_{config_name}.md")
-    src = os.path.join(ROOT, "paper_2604_06483_amd", "csrc", "ll_project.hip")
-    if not (os.path.exists(path) and os.path.exists(src)):
+    csrc = os.path.join(ROOT, "paper_2604_06483_amd", "csrc")
+    srcs = [os.path.join(csrc, f) for f in ("ll_gemm_lds.h", "ll_epilogue.h")]     # the timed kernel and its epilogue
+    if not (os.path.exists(path) and all(os.path.exists(f) for f in srcs)):
         return None
     text = open(path).read()
     m_t = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
     m_h = re.search(r"^kernel_source_sha256:\s*([0-9a-f]{64})", text, re.M)
     if not (m_t and m_h):
         return None
-    if hashlib.sha256(open(src, "rb").read()).hexdigest() != m_h.group(1):
+    h = hashlib.sha256()
+    for f in srcs:
+        h.update(open(f, "rb").read())
+    if h.hexdigest() != m_h.group(1):
         return None
     return float(m_t.group(1))
 

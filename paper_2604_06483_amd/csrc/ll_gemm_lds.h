@@ -1,0 +1,347 @@
+// Direct-to-LDS projection kernel (d a multiple of 64; operands by global_load_lds into LDS rings,
+// v_mfma_f32_16x16x32_bf16): the kernel the benchmark times.
+#pragma once
+
+#include "ll_epilogue.h"
+
+namespace {
+
+// ---------------------------------------------------------------------------------------
+// Direct-to-LDS kernel: both operands go from global memory straight into LDS (global_load_lds,
+// 16 bytes per lane) in stages of K = 64, so that every load instruction takes whole 128-byte
+// lines (8 rows x 128 B).  A must be a panel of already normalised bf16 rows with row stride
+// lda, a multiple of 64, zero padded beyond d (the norm kernel above writes it); W rows are read
+// in place.
+//
+// LDS holds five 32 KB slots, each one operand tile [256 rows][128 B]: a ring of three for the
+// W tiles (stage g in slot g % 3) and a ring of two for the A tiles (stage g in slot 3 + g % 2).
+// The 16-byte chunk index is XOR-swizzled with (row/2)%8, which makes the 8 rows x 8 chunks that
+// one load instruction writes (1 KB, lane-linear) and the 16 rows x 4 chunks that a fragment read
+// touches both bank-conflict free.
+//
+// The matrix instruction here is v_mfma_f32_16x16x32_bf16 (vocabulary on the M side as in the
+// other kernel: 16 x 4 accumulator tiles of 16 x 16 per wavefront).  At the same rate it moves
+// half the accumulator bytes per flop of the 32x32x16 form, and on this power-limited chip that
+// is worth 11 % on a bare MFMA loop and 4 % on this kernel.
+//
+// Wavefront w loads rows [64w, 64w+64) of every tile.  Of a W tile it reads all rows, so W slots
+// change hands at a workgroup barrier; of an A tile it reads exactly the rows it loaded itself,
+// so an A slot is the wavefront's own again as soon as its last fragment of the stage is in
+// registers, with no barrier.  That is what the two rings are for: the A fragments of a whole
+// stage are read early (32 registers), and both streams get about two stages between sending a
+// load and needing its data, from the same 160 KB.
+//
+// Schedule of stage g, four slices of 32 MFMAs: (K half 0, vocabulary tiles 0-7), (0, 8-15),
+// (1, 0-7), (1, 8-15); W fragments alternate between two register sets of eight:
+//   slice 0    : reads the W fragments of slice 1 and the A fragments of K half 1 (the last of
+//                the stage: the wavefront's rows of A(g)'s slot are free); sends the second half
+//                of W(g+2);
+//   slices 1, 2: read the W fragments of the next slice; send A(g+2), half each;
+//   wait + barrier: all loads but the last 16 (W(g+2), A(g+2)) have landed, so stage g+1 is in
+//                LDS for everyone, and everyone holds its last fragments of W(g): that slot is free;
+//   slice 3    : reads the W fragments of slice 0 and the A fragments of K half 0 of stage g+1;
+//                sends the first half of W(g+3) into the slot of W(g).
+// Four loads per slice, one behind every eighth MFMA, keep the load pipe evenly fed and the
+// wavefront's issue slots free for the matrix pipe.  The rings are fed unconditionally and run on
+// across vocabulary tiles (the next tile's first stages load under the epilogue); past the last
+// real stage they re-fetch the last tile, never consumed, which keeps the count of loads in
+// flight, and with it the s_waitcnt, constant.
+// ---------------------------------------------------------------------------------------
+constexpr int DK = 64;
+constexpr int W_SLOTS = 3, A_SLOTS = 2, SLOTS = W_SLOTS + A_SLOTS;
+constexpr int SLOT_BYTES = 256 * DK * 2;
+constexpr int LOADS_PER_TILE = 8;    // per wavefront: 8 segments of 1 KB of one operand tile
+// s_waitcnt immediate (gfx9 layout): vmcnt in bits 3:0 and 15:14, expcnt 6:4 (7 = no wait), lgkmcnt 11:8.
+constexpr int waitcnt_imm(int vmcnt, int lgkmcnt) { return (vmcnt & 0xF) | ((vmcnt >> 4) << 14) | 0x70 | (lgkmcnt << 8); }
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// One global_load_lds_dwordx4: every lane fetches 16 bytes from base + off + IMM and the
+// wavefront's 1 KB lands lane-linear at LDS byte address M0 + IMM (the instruction's immediate
+// offset moves both addresses).  Written as an instruction rather than through the builtin: the
+// compiler cannot tell which LDS bytes a builtin load-to-LDS writes, so it makes every later LDS
+// read wait for ALL loads in flight, which would serialise the ring; here all waits are the
+// explicit s_waitcnt of the main loop.  One instruction per load, with the LDS base set once per
+// tile, matters: a wavefront alone on its SIMD issues one instruction every four cycles or so, and
+// whatever sits between two MFMAs beyond the 16 cycles the first one runs leaves the pipe idle.
+template <int IMM>
+__device__ __forceinline__ void load_to_lds_16(const unsigned char* base, unsigned off) {
+  static_assert(IMM >= -4096 && IMM < 4096, "13-bit signed immediate");
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(off), "s"(base), "n"(IMM) : "memory");
+}
+
+// LDS base of the loads that follow.  M0 is the compiler's own scratch register: it sets it right
+// before each of its own uses and keeps nothing in it, and it knows from the clobber that this
+// statement writes it.  Nothing in the main loop below (MFMA, ds_read, s_waitcnt, s_barrier)
+// makes the compiler use M0, so the value holds from here to the last load of the tile.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void set_lds_dma_base(unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(lds_addr) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+  return c;
+}
+
+template <class EPI>
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void ll_lens_gemm_dma_kernel(const GemmArgs p) {
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int logical = xcd_logical_block();
+  if (logical >= p.row_blocks * p.splits) return;
+  const int split = logical % p.splits;
+  const int rb = logical / p.splits;
+  const int tile0 = (int)((int64_t)split * p.tiles / p.splits);
+  const int tile1 = (int)((int64_t)(split + 1) * p.tiles / p.splits);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int d = p.d, V = p.V;
+  const int lda = (int)p.lda;
+  const int KT = lda / DK;
+
+  // --- DMA map.  One load instruction fills 8 rows x 128 B; lane l lands at row l/8, physical
+  // chunk l%8.  Wavefront w fills rows [64w, 64w+64) of a tile in 8 segments; segment s holds
+  // rows 64w + 8s + l/8, whose swizzle is (l/16 + 4s) % 8, so the lane fetches logical chunk
+  // (l%8) ^ (l/16) ^ 4(s%2).  M0 points at the middle of the wavefront's 8 KB and segment s uses
+  // the immediate (s-4) KB; since the immediate also moves the global address, the lane's byte
+  // offset carries the opposite shift, plus 7 KB so that it cannot go below zero, and the
+  // wave-uniform base (tile, K step) starts 3 KB early: base + off + imm is the chunk's address.
+  const int seg_row = 64 * wave + (lane >> 3);                        // + 8 s
+  const int seg_koff0 = ((lane & 7) ^ (lane >> 4)) * 8;               // element offset, even segments
+  const int seg_koff1 = seg_koff0 ^ 32;                               // odd segments
+  const int a_last = p.rows - 1 - rb * BN;                            // last valid row of this block
+  constexpr int IMM_BIAS = 3072;                                      // largest immediate, segment 7
+
+  // Per-lane byte offsets of the 8 segments, fixed for the whole sweep (W: per vocabulary tile,
+  // because the last tile clamps its rows to V-1): one load is one instruction.
+  unsigned a_off[8], w_off[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s)
+    a_off[s] = (unsigned)(min(seg_row + 8 * s, a_last) * lda + ((s & 1) ? seg_koff1 : seg_koff0)) * 2u + (7168u - 1024u * s);
+  auto set_w_rows = [&](int tile) {
+    const int w_last = V - 1 - tile * BM;
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+      w_off[s] = (unsigned)(min(seg_row + 8 * s, w_last) * d + ((s & 1) ? seg_koff1 : seg_koff0)) * 2u + (7168u - 1024u * s);
+  };
+
+  // Producer state of the two operand streams, all wave-uniform and moved on by a few scalar
+  // instructions per stage.
+  const unsigned lds_mid = (unsigned)(uintptr_t)(lptr_t)smem + wave * (64 * DK * 2) + 4096;
+  const unsigned w_lds_wrap = lds_mid + W_SLOTS * SLOT_BYTES;
+  const unsigned a_lds_flip = (2 * W_SLOTS + 1) * SLOT_BYTES + 2 * lds_mid;   // slot 3 <-> slot 4
+  const unsigned char* const a_base0 = reinterpret_cast<const unsigned char*>(p.A + (int64_t)rb * BN * lda) - IMM_BIAS;
+  auto w_tile_base = [&](int tile) {
+    return reinterpret_cast<const unsigned char*>(p.W + (int64_t)tile * BM * d) - IMM_BIAS;
+  };
+  // (LL_PIN_S: the value is computed where the statement stands; without it the compiler gathers
+  // the scalar updates of a whole stage into one lump, and the matrix pipe idles behind it.)
+#define LL_PIN_S(x) asm volatile("" : "+s"(x))
+  int w_tile = tile0, w_kt = 0, a_kt = 0;
+  unsigned w_lds = lds_mid, a_lds = lds_mid + W_SLOTS * SLOT_BYTES;   // M0 value of the stream's next tile
+  const unsigned char* w_base = w_tile_base(tile0);
+  const unsigned char* a_base = a_base0;
+  set_w_rows(tile0);
+  auto advance_w = [&]() {
+    w_lds += SLOT_BYTES;
+    if (w_lds >= w_lds_wrap) w_lds -= W_SLOTS * SLOT_BYTES;
+    w_base += DK * 2;
+    if (++w_kt == KT) {   // next vocabulary tile; past the end of the sweep the ring refetches the last one
+      w_kt = 0;
+      ++w_tile;
+      const int t = w_tile < tile1 ? w_tile : tile1 - 1;
+      set_w_rows(t);
+      w_base = w_tile_base(t);
+    }
+    LL_PIN_S(w_lds);
+    LL_PIN_S(w_base);
+  };
+  auto advance_a = [&]() {
+    a_lds = a_lds_flip - a_lds;
+    a_base += DK * 2;
+    if (++a_kt == KT) {
+      a_kt = 0;
+      a_base = a_base0;
+    }
+    LL_PIN_S(a_lds);
+    LL_PIN_S(a_base);
+  };
+#define LL_DMA_W(S) load_to_lds_16<((S) - 4) * 1024>(w_base, w_off[S])
+#define LL_DMA_A(S) load_to_lds_16<((S) - 4) * 1024>(a_base, a_off[S])
+#define LL_DMA_TILE(DMA) DMA(0); DMA(1); DMA(2); DMA(3); DMA(4); DMA(5); DMA(6); DMA(7)
+
+  // --- MFMA fragment map (v_mfma_f32_16x16x32_bf16): lane reads row (lane % 16) of each 16-row
+  // group; of the two K = 32 halves of a stage, half hk is the logical 16-byte chunks
+  // 4 hk + lane/16 of the row.
+  const int f_row = lane & 15;
+  const int f_grp = lane >> 4;
+  const int f_swz = (f_row >> 1) & 7;
+  int f_off[2];
+#pragma unroll
+  for (int hk = 0; hk < 2; ++hk) f_off[hk] = f_row * (DK * 2) + (((4 * hk + f_grp) ^ f_swz) * 16);
+  const int a_wave_off = (wave * 64) * (DK * 2);
+
+  const int my_row = rb * BN + tid;
+  typename EPI::State st;
+  EPI::init(st, p, my_row);
+
+  // prologue: W0 A0 W1 A1 and the first half of W2 in flight; stage 0 landed
+  set_lds_dma_base(w_lds);
+  LL_DMA_TILE(LL_DMA_W);
+  advance_w();
+  set_lds_dma_base(a_lds);
+  LL_DMA_TILE(LL_DMA_A);
+  advance_a();
+  set_lds_dma_base(w_lds);
+  LL_DMA_TILE(LL_DMA_W);
+  advance_w();
+  set_lds_dma_base(a_lds);
+  LL_DMA_TILE(LL_DMA_A);
+  advance_a();
+  set_lds_dma_base(w_lds);
+  LL_DMA_W(0); LL_DMA_W(1); LL_DMA_W(2); LL_DMA_W(3);
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE + 4, 15));   // W0 and A0 landed
+  __syncthreads();
+  // A: the four row tiles of both K halves of the stage; W: two sets of eight vocabulary tiles of one half
+  bf16x8 fa[2][4], fw0[8], fw1[8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    fa[0][j] = *reinterpret_cast<const bf16x8*>(smem + W_SLOTS * SLOT_BYTES + a_wave_off + j * 16 * (DK * 2) + f_off[0]);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) fw0[i] = *reinterpret_cast<const bf16x8*>(smem + i * 16 * (DK * 2) + f_off[0]);
+
+  // A stage is four slices of 32 MFMAs: (K half 0, vocabulary tiles 0-7), (0, 8-15), (1, 0-7),
+  // (1, 8-15).  One slice: eight vocabulary tiles (fragments fw) against the four row tiles of a
+  // K half (fah), accumulators MB .. MB+7.  An MFMA runs for 16 cycles, so a gap between two of
+  // them holds at most two or three other instructions: behind the first MFMA of a row of four
+  // goes the LDS read of one W fragment of the next slice (into nw, from LDS offset tW),
+  // behind the second an A fragment read (RHOOK), behind the third a load-to-LDS or a piece of
+  // the streams' bookkeeping (HOOK).  The fences pin that order.
+#define LL_LDS_FRAG(ptr) (*reinterpret_cast<const bf16x8*>(ptr))
+  // Written as an instruction so that the 64 accumulator tiles stay in AGPRs: given the builtin,
+  // the register allocator keeps some of them in VGPRs and copies them in and out around the MFMA.
+  // (Operands come from LDS reads, whose waits the compiler still places; nothing reads an
+  // accumulator before the epilogue's own drain.)
+#define LL_MFMA16(a, b, c) mfma16(a, b, c)
+#define LL_ROW(I, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                        \
+  acc[MB + I][0] = LL_MFMA16(fw[I], fah[0], acc[MB + I][0]);                                         \
+  nw[I] = LL_LDS_FRAG(smem + tW + (NMB + I) * 16 * (DK * 2) + (off));                                \
+  LL_SCHED_FENCE();                                                                                  \
+  acc[MB + I][1] = LL_MFMA16(fw[I], fah[1], acc[MB + I][1]);                                         \
+  RHOOK(I);                                                                                          \
+  LL_SCHED_FENCE();                                                                                  \
+  acc[MB + I][2] = LL_MFMA16(fw[I], fah[2], acc[MB + I][2]);                                         \
+  HOOK(I);                                                                                           \
+  LL_SCHED_FENCE();                                                                                  \
+  acc[MB + I][3] = LL_MFMA16(fw[I], fah[3], acc[MB + I][3]);                                         \
+  LL_SCHED_FENCE();
+#define LL_SLICE(MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                         \
+  LL_SCHED_FENCE();                                                                                  \
+  LL_ROW(0, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(1, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(2, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(3, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(4, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(5, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(6, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(7, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)
+
+#define LL_RHOOK_NONE(I) (void)0
+  // slice 0 fetches the A fragments of the stage's second K half (the last of A(g) this wavefront
+  // needs), slice 3 those of the next stage's first half
+#define LL_RHOOK_S0(I) \
+  if (I < 4) fa[1][I & 3] = LL_LDS_FRAG(smem + cA + (I & 3) * 16 * (DK * 2) + f_off[1])
+#define LL_RHOOK_S3(I) \
+  if (I < 4) fa[0][I & 3] = LL_LDS_FRAG(smem + nA + (I & 3) * 16 * (DK * 2) + f_off[0])
+#define LL_HOOK_S0(I)                                \
+  if (I == 0) set_lds_dma_base(w_lds);               \
+  if (I == 3) LL_DMA_W(4);                           \
+  if (I == 4) LL_DMA_W(5);                           \
+  if (I == 5) LL_DMA_W(6);                           \
+  if (I == 6) LL_DMA_W(7);                           \
+  if (I == 7) advance_w()
+  // (the last A fragments of the stage were read early in slice 0, and LDS reads return in order:
+  // once slice 1 has its first W fragment, A(g)'s slot is the wavefront's own)
+#define LL_HOOK_S1(I)                                \
+  if (I == 3) set_lds_dma_base(a_lds);               \
+  if (I == 4) LL_DMA_A(0);                           \
+  if (I == 5) LL_DMA_A(1);                           \
+  if (I == 6) LL_DMA_A(2);                           \
+  if (I == 7) LL_DMA_A(3)
+#define LL_HOOK_S2(I)                                \
+  if (I == 2) LL_DMA_A(4);                           \
+  if (I == 3) LL_DMA_A(5);                           \
+  if (I == 4) LL_DMA_A(6);                           \
+  if (I == 5) LL_DMA_A(7);                           \
+  if (I == 6) advance_a()
+#define LL_HOOK_S3(I)                                \
+  if (I == 3) set_lds_dma_base(w_lds);               \
+  if (I == 4) LL_DMA_W(0);                           \
+  if (I == 5) {                                      \
+    LL_DMA_W(1);                                     \
+    nnW = nW + SLOT_BYTES >= W_SLOTS * SLOT_BYTES ? 0 : nW + SLOT_BYTES;   \
+    LL_PIN_S(nnW);                                   \
+  }                                                  \
+  if (I == 6) {                                      \
+    LL_DMA_W(2);                                     \
+    const int t_ = cA;                               \
+    cA = nA;                                         \
+    nA = t_;                                         \
+  }                                                  \
+  if (I == 7) {   /* every row of the slice reads a W fragment from nW: move on after the last */ \
+    LL_DMA_W(3);                                     \
+    cW = nW;                                         \
+    nW = nnW;                                        \
+  }
+
+  // Consumer state: LDS byte offsets of the W and A tiles of this stage and of the next (the A
+  // offsets include the wavefront's own 64 rows).
+  int cW = 0, nW = SLOT_BYTES, nnW = 2 * SLOT_BYTES;
+  int cA = W_SLOTS * SLOT_BYTES + a_wave_off, nA = (W_SLOTS + 1) * SLOT_BYTES + a_wave_off;
+  for (int tile = tile0; tile < tile1; ++tile) {
+    f32x4 acc[16][4];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+
+    for (int kt = 0; kt < KT; ++kt) {
+      LL_SLICE(0, fw0, fa[0], fw1, cW, 8, f_off[0], LL_RHOOK_S0, LL_HOOK_S0)
+      LL_SLICE(8, fw1, fa[0], fw0, cW, 0, f_off[1], LL_RHOOK_NONE, LL_HOOK_S1)
+      LL_SLICE(0, fw0, fa[1], fw1, cW, 8, f_off[1], LL_RHOOK_NONE, LL_HOOK_S2)
+      // stage g+1 landed (W(g+2) and A(g+2) may still be out); all my reads of W(g) are done
+      __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE, 0));
+      __syncthreads();
+      LL_SLICE(8, fw1, fa[1], fw0, nW, 0, f_off[0], LL_RHOOK_S3, LL_HOOK_S3)
+    }
+    EPI::tile(acc, st, tile * BM, p);
+  }
+#undef LL_SLICE
+#undef LL_ROW
+#undef LL_MFMA16
+#undef LL_LDS_FRAG
+#undef LL_DMA_TILE
+#undef LL_HOOK_S3
+#undef LL_RHOOK_S3
+#undef LL_RHOOK_S0
+#undef LL_RHOOK_NONE
+#undef LL_PIN_S
+#undef LL_HOOK_S2
+#undef LL_HOOK_S1
+#undef LL_HOOK_S0
+#undef LL_DMA_A
+#undef LL_DMA_W
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));   // drain the ring before the LDS is given back
+  EPI::store(p, st, my_row, split);
+}
+
+}  // namespace
