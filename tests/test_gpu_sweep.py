@@ -47,6 +47,7 @@ def compare_sweep(got, want, rows, label):
     (257, 128, 777, 3, True),        # few alphas, odd vocabulary
     (520, 1024, 33000, 5, False),    # rows already normalised, many tiles per split
     (40, 64, 300, 1, True),          # a single alpha, one K step
+    (9000, 128, 1000, 2, True),      # two row passes: the second starts at row 8192 of every output
 ])
 def test_sweep_matches_oracle(N, d, V, n_alpha, gamma):
     say(f"sweep N={N} d={d} V={V} A={n_alpha} gamma={gamma}")
