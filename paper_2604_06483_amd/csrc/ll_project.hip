@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void ll_sweep_merge_kernel(const float4* __res
                                                              float* __restrict__ out_entropy);
 
 // ---------------------------------------------------------------------------------------
-// a8: merge the splits of each row and finalise.  One thread per row.
+// a8: merge the splits of each row and finalise.  One wavefront per row, one lane per split.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ float wave_max(float x) {
 #pragma unroll
