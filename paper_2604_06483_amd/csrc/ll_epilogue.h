@@ -257,9 +257,11 @@ __device__ __forceinline__ void epilogue_group(const ACC& acc, RowState<KR>& st,
   st.s += (s4[0] + s4[1]) + (s4[2] + s4[3]);
   st.t += (t4[0] + t4[1]) + (t4[2] + t4[3]);
 
-  // a6: streaming top-k.  Only when some lane of the wavefront has a logit above its current
-  // KR-th best: mark the candidates against that threshold, then insert them in id order.
-  if (__builtin_amdgcn_ballot_w64(gmax > st.tau()) != 0) {
+  // a6: streaming top-k.  Only the lanes with a logit above their current KR-th best take part
+  // (a divergent branch: the other lanes are masked off and cost no energy, which is what counts
+  // on a power-limited chip): mark the candidates against that threshold, then insert them in
+  // id order.
+  if (gmax > st.tau()) {
     const float tau0 = st.tau();
     // bit o of mask: x[o] > tau0.  Two instructions per entry: the comparison, then the mask
     // doubled plus the comparison's result as carry-in (entries taken from 31 down to 0).  Four
@@ -382,19 +384,17 @@ __device__ __forceinline__ void sweep_group(const ACC& acc, SweepState& st, int 
       float gmax = y[0];
 #pragma unroll
       for (int o = 1; o < 32; ++o) gmax = fmaxf(gmax, y[o]);
-      if (__builtin_amdgcn_ballot_w64(gmax > st.m[a]) != 0) {
-        // a new maximum for some lane: ids come in increasing order, so strictly greater is the
+      if (gmax > st.m[a]) {
+        // a new maximum for this lane: ids come in increasing order, so strictly greater is the
         // tie rule, and within the group the lowest position with that value wins
-        const bool up = gmax > st.m[a];
         int pos = 0;
 #pragma unroll
         for (int o = 31; o >= 0; --o) pos = (y[o] == gmax) ? o : pos;
-        const float m_new = fmaxf(st.m[a], gmax);
-        const float sc = __builtin_amdgcn_exp2f((st.m[a] - m_new) * LOG2E);   // first group: exp2(-inf) = 0
+        const float sc = __builtin_amdgcn_exp2f((st.m[a] - gmax) * LOG2E);   // first group: exp2(-inf) = 0
         st.s[a] *= sc;
         st.t[a] *= sc;
-        st.m[a] = m_new;
-        st.id[a] = up ? g0 + pos : st.id[a];
+        st.m[a] = gmax;
+        st.id[a] = g0 + pos;
       }
       const float mb = st.m[a] * LOG2E;
       float s4[4] = {0.f, 0.f, 0.f, 0.f}, t4[4] = {0.f, 0.f, 0.f, 0.f};
