@@ -263,3 +263,45 @@ def test_full_size_config_sampled_rows(name, gemm_path):
     assert abs(float(np.mean(got["entropy"][rows])) - float(np.mean(pred))) < 0.05
     del w
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------------------------------
+# the projection allocates nothing and never synchronises: it can be captured in a HIP graph
+# ------------------------------------------------------------------------------------------
+def test_projection_replays_from_a_hip_graph(gemm_path):
+    if gemm_path != 2:
+        pytest.skip("one kernel path is enough for this property")
+    LL.ll_set_gemm_path(0)
+    say("graph capture")
+    cfg = WL.LensConfig("graph", L=2, T=300, d=256, V=5000, k=10, n_outliers=4, outlier_scale=20.0)
+    w = WL.make_workload(cfg, DEV, seed=4)
+    N = cfg.N
+    ws = torch.empty(LL.ll_workspace_bytes(N, cfg.d, cfg.V, cfg.k), dtype=torch.uint8, device=DEV)
+    out = (torch.zeros((N, cfg.k), dtype=torch.int32, device=DEV), torch.zeros((N, cfg.k), dtype=torch.float32, device=DEV),
+           torch.zeros((N,), dtype=torch.float32, device=DEV), torch.zeros((N,), dtype=torch.float32, device=DEV))
+    hidden = w.hidden.clone()
+    eager = [t.clone() for t in LL.ll_project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids)]
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        LL.ll_project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, out=out, stream=s)   # warm-up
+        s.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            LL.ll_project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, out=out, stream=s)
+    for rep in range(3):
+        for t in out:
+            t.zero_()
+        ws.zero_()                                   # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(out, eager):
+            assert torch.equal(got, want), f"replay {rep} differs from the eager result"
+    # new input in the captured buffer, same graph
+    hidden.copy_(torch.flip(w.hidden, dims=(1,)))
+    want = [t.clone() for t in LL.ll_project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids)]
+    g.replay()
+    torch.cuda.synchronize()
+    for got, w_ in zip(out, want):
+        assert torch.equal(got, w_)
