@@ -81,8 +81,8 @@ def cpu_baseline(w, gpu_np, R):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="llama31-70b")
     ap.add_argument("--sample-rows", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
