@@ -90,3 +90,14 @@ def test_steer_rows():
     assert base.shape == (64, 256) and target.shape == (64, 256) and l_star == 2
     assert base.dtype == torch.bfloat16
     assert float((target.float().mean(0) - base.float().mean(0)).norm()) > 1.0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus N with N > 1 exits with a message that says so (no GPU needed for this)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0
+    assert "ONE GPU" in (res.stdout + res.stderr)
