@@ -67,6 +67,20 @@ __global__ __launch_bounds__(256) void ll_steer_colsum_kernel(const uint16_t* __
   }
 }
 
+// Many slices: one thread per column sums them (consecutive threads, consecutive columns) and
+// writes the difference of means; the one-workgroup finish below then only normalises.
+__global__ __launch_bounds__(256) void ll_steer_reduce_kernel(const float* __restrict__ part, int slices, int64_t n_base,
+                                                              int64_t n_target, int d, float* __restrict__ out_v) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= d) return;
+  float sb = 0.f, st = 0.f;
+  for (int s = 0; s < slices; ++s) {
+    sb += part[(int64_t)s * d + c];
+    st += part[((int64_t)slices + s) * d + c];
+  }
+  out_v[c] = st / (float)n_target - sb / (float)n_base;
+}
+
 // Finish: (sum the slices,) form the difference of means, L2-normalise.  One workgroup.
 template <bool DIRECT>
 __global__ __launch_bounds__(1024) void ll_steer_finish_kernel(const float* __restrict__ part, int slices, int64_t n_base,
@@ -282,8 +296,16 @@ int ll_steer_vector(const void* base, int64_t n_base, const void* target, int64_
     hipLaunchKernelGGL(ll_steer_colsum_kernel<false>, dim3(col_blocks, slices), dim3(256), 0, stream, b, n_base, t, n_target,
                        d, slices, part);
     LL_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(ll_steer_finish_kernel<false>, dim3(1), dim3(1024), 0, stream, (const float*)part, slices, n_base,
-                       n_target, d, normalize, out_v);
+    if (slices <= 8) {
+      hipLaunchKernelGGL(ll_steer_finish_kernel<false>, dim3(1), dim3(1024), 0, stream, (const float*)part, slices, n_base,
+                         n_target, d, normalize, out_v);
+    } else {   // same sums in the same order, spread over the chip
+      hipLaunchKernelGGL(ll_steer_reduce_kernel, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, stream, (const float*)part,
+                         slices, n_base, n_target, d, out_v);
+      LL_HIP_CHECK(hipGetLastError());
+      hipLaunchKernelGGL(ll_steer_finish_kernel<true>, dim3(1), dim3(1024), 0, stream, (const float*)nullptr, 1, n_base,
+                         n_target, d, normalize, out_v);
+    }
     LL_HIP_CHECK(hipGetLastError());
   }
   return LL_OK;
