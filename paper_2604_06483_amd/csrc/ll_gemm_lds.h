@@ -10,7 +10,7 @@ namespace {
 // Direct-to-LDS kernel: both operands go from global memory straight into LDS (global_load_lds,
 // 16 bytes per lane) in stages of K = 64, so that every load instruction takes whole 128-byte
 // lines (8 rows x 128 B).  A must be a panel of already normalised bf16 rows with row stride
-// lda, a multiple of 64, zero padded beyond d (the norm kernel above writes it); W rows are read
+// lda, a multiple of 64, zero padded beyond d (ll_norm_panel_kernel writes it); W rows are read
 // in place.
 //
 // LDS holds five 32 KB slots, each one operand tile [256 rows][128 B]: a ring of three for the
