@@ -61,8 +61,8 @@ size_t ll_workspace_bytes(const ll_shape* shape, int k);
  *   target_ids  int32 [N], or NULL: out_target_logp is not written (and may be NULL)
  *   workspace   device scratch of at least ll_workspace_bytes(shape, k) bytes, 256-byte aligned
  *
- * Requirements: d a positive multiple of 8, 1 <= k <= min(LL_KMAX, V), all tensors 16-byte
- * aligned.  N == 0 is a successful no-op.  Rows are processed in passes of at most 8192 rows
+ * Requirements: d a positive multiple of 8, V at most 2^31 - 257, 1 <= k <= min(LL_KMAX, V), all
+ * tensors 16-byte aligned.  N == 0 is a successful no-op.  Rows are processed in passes of at most 8192 rows
  * so the workspace does not grow with N beyond 4 bytes per row.
  * Arithmetic: bf16 operands, fp32 accumulation and fp32 softmax statistics.
  * Everything is enqueued on `stream`; the call returns without waiting.
@@ -210,7 +210,8 @@ int ll_steer_sweep(const ll_shape* shape, void* workspace, size_t workspace_byte
                    void* stream);
 
 /*
- * Chooses the projection kernel for later ll_project calls of this process (not thread safe):
+ * Chooses the projection kernel for ll_project calls of this process that start afterwards
+ * (one process-wide setting; a call already running keeps the kernel it chose):
  *   0  automatic (default)
  *   1  register-staged kernel: the RMSNorm scaling is applied inside the A-tile load of the GEMM
  *   2  direct-to-LDS kernel fed from a normalised bf16 panel written once per row pass

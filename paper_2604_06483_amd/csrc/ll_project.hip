@@ -8,6 +8,8 @@
 #include "ll_gemm_lds.h"
 #include "ll_gemm_staged.h"
 
+#include <atomic>
+#include <climits>
 #include <type_traits>
 #include <vector>
 
@@ -282,6 +284,8 @@ struct Plan {
 bool shape_ok(const ll_shape* s, int k) {
   if (s == nullptr) return false;
   if (s->N < 0 || s->d <= 0 || s->V <= 0 || (s->d & 7) != 0) return false;
+  // rounding up to whole tiles (V) and whole K stages (d) stays inside 32 bits
+  if (s->V > INT32_MAX - BM || s->d > INT32_MAX - 2 * DK) return false;
   if (k < 1 || k > LL_KMAX || k > s->V) return false;
   return true;
 }
@@ -306,7 +310,7 @@ Plan make_plan(const ll_shape* s, int k) {
 
 // 0: automatic; 1: register-staged kernel with the norm fused into the A-tile load; 2: direct-to-LDS
 // kernel fed from a normalised panel.
-int g_gemm_path = 0;
+std::atomic<int> g_gemm_path{0};
 
 int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
                  const void* W_U, const float* bias, unsigned flags, float eps, int k, const int32_t* target_ids,
@@ -340,7 +344,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   const bool dma_ok = d % DK == 0 && (int64_t)BM * d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * plan.lda * 2 < (int64_t)1 << 31;
   // A bias (rare: the paper's model families have none) goes through the register-staged kernel,
   // so that the fast kernel carries no code or registers for it.
-  const bool dma = g_gemm_path != 1 && dma_ok && bias == nullptr;
+  const bool dma = g_gemm_path.load(std::memory_order_relaxed) != 1 && dma_ok && bias == nullptr;
   const size_t lds = dma ? (size_t)SLOTS * SLOT_BYTES : (size_t)(BM + BN) * BK * 2;
   // The top-k lists live in registers: the kernels are built for a few list lengths KR >= k.
   void (*kern)(const GemmArgs);
@@ -596,7 +600,7 @@ int ll_steer_sweep(const ll_shape* shape, void* workspace, size_t workspace_byte
 
 int ll_set_gemm_path(int path) {
   if (path < 0 || path > 2) return LL_EINVAL;
-  g_gemm_path = path;
+  g_gemm_path.store(path, std::memory_order_relaxed);
   return LL_OK;
 }
 

@@ -51,6 +51,8 @@ def test_workspace_arithmetic():
     assert LL.ll_workspace_bytes(10, 64, 4, 5) == 0             # k > V
     assert LL.ll_workspace_bytes(-1, 64, 100, 5) == 0
     assert LL.ll_workspace_bytes(0, 64, 100, 5) > 0
+    assert LL.ll_workspace_bytes(10, 64, 2 ** 31 - 1, 5) == 0   # rounding V up to whole tiles would leave 32 bits
+    assert LL.ll_workspace_bytes(10, 64, 2 ** 31 - 257, 5) > 0
     # grows with k, is bounded in N beyond one pass (only 4 bytes per extra row)
     a = LL.ll_workspace_bytes(8192, 8192, 128256, 20)
     b = LL.ll_workspace_bytes(121500, 8192, 128256, 20)
