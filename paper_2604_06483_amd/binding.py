@@ -100,6 +100,16 @@ def _stream(stream):
     return c_void_p(s.cuda_stream)
 
 
+def _scratch(nbytes, device, stream):
+    """A workspace of this call's own.  It is released when the call returns, while the kernels may
+    still be queued: tell the allocator which stream uses it, so that the block is not handed to
+    another stream's tensor before they have run."""
+    ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    if stream is not None:
+        ws.record_stream(stream)
+    return ws
+
+
 def ll_set_gemm_path(path: int) -> None:
     rc = lib().ll_set_gemm_path(int(path))
     if rc != LL_OK:
@@ -136,7 +146,7 @@ def ll_project(hidden, gamma, W_U, eps, k, target_ids=None, *, workspace=None, s
     shape = ll_shape(N, d, V)
     need = int(lib().ll_workspace_bytes(shape, k))
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=hidden.device)
+        workspace = _scratch(need, hidden.device, stream)
     dev = hidden.device
     if out is None:
         ids = torch.empty((N, k), dtype=torch.int32, device=dev)
@@ -227,7 +237,7 @@ def ll_steer_sweep(hidden, gamma, W_U, eps, v, alphas, target_ids=None, *, works
     shape = ll_shape(N, d, V)
     need = int(lib().ll_steer_sweep_workspace_bytes(shape, A))
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=hidden.device)
+        workspace = _scratch(need, hidden.device, stream)
     dev = hidden.device
     ids = torch.empty((A, N), dtype=torch.int32, device=dev)
     p = torch.empty((A, N), dtype=torch.float32, device=dev)
