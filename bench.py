@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="llama31-70b")
-    ap.add_argument("--sample-rows", type=int, default=512)
+    ap.add_argument("--sample-rows", type=int, default=1024)   # ~12 s of host time on 16 cores
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for rocprofv3's "
