@@ -170,6 +170,16 @@ __device__ __forceinline__ int wave_min_int(int x) {
   for (int off = 32; off > 0; off >>= 1) x = min(x, __shfl_xor(x, off, kWave));
   return x;
 }
+// The same over the first `width` lanes only (a power of two; every lane below it gets the result):
+// the k steps of the merge are a chain of these exchanges, and with eight splits three rounds do.
+__device__ __forceinline__ float group_max(float x, int width) {
+  for (int off = width >> 1; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, kWave));
+  return x;
+}
+__device__ __forceinline__ int group_min_int(int x, int width) {
+  for (int off = width >> 1; off > 0; off >>= 1) x = min(x, __shfl_xor(x, off, kWave));
+  return x;
+}
 
 // One wavefront per row, lane s = split s (splits <= 64).
 __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict__ stats, const uint2* __restrict__ top,
@@ -209,9 +219,11 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict_
   }
   float z0 = 0.f, sk = 0.f;   // top-k-only softmax: the largest selected logit and the sum over the selection
   float mine = 0.f;           // lane j keeps the j-th selected logit
+  int width = 1;   // lanes that hold a list, rounded up to a power of two (lanes past `splits` hold the neutral head)
+  while (width < splits) width <<= 1;
   for (int j = 0; j < k; ++j) {
-    const float bz = wave_max(z);
-    const int bi = wave_min_int(z == bz ? id : INT_MAX);
+    const float bz = group_max(z, width);
+    const int bi = group_min_int(z == bz ? id : INT_MAX, width);
     if (live && z == bz && id == bi) {   // ids are distinct: exactly one lane
       ++head;
       if (head < k) {
@@ -223,12 +235,14 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict_
         id = INT_MAX;
       }
     }
-    if (j == 0) z0 = bz;
-    sk += __builtin_amdgcn_exp2f((bz - z0) * LOG2E);
-    if (lane == j) mine = bz;
+    // (lanes past `width` did not take part: what they keep comes from lane 0)
+    const float out_z = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(bz)));
+    if (j == 0) z0 = out_z;
+    sk += __builtin_amdgcn_exp2f((out_z - z0) * LOG2E);
+    if (lane == j) mine = out_z;
     if (lane == 0) {
       out_ids[(int64_t)row * k + j] = bi;
-      if (!topk_softmax) out_p[(int64_t)row * k + j] = __builtin_amdgcn_exp2f(((bz - M) - logS) * LOG2E);
+      if (!topk_softmax) out_p[(int64_t)row * k + j] = __builtin_amdgcn_exp2f(((out_z - M) - logS) * LOG2E);
     }
   }
   // The paper's own probabilities (Sec. 3.3): a softmax over the k selected logits only.
