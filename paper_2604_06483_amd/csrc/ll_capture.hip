@@ -43,6 +43,7 @@ int ll_capture_append(const ll_capture_shape* shape, void* store, const void* sl
   if (shape == nullptr || shape->L <= 0 || shape->C <= 0 || shape->T <= 0 || shape->d <= 0 || (shape->d & 7) != 0)
     return LL_EINVAL;
   if (t0 < 0 || n_tok < 0 || t0 > shape->T || n_tok > shape->T - t0) return LL_EINVAL;
+  if ((int64_t)shape->L * shape->C > INT64_MAX / shape->T) return LL_EINVAL;   // the store's row count fits 64 bits
   if (n_tok == 0) return LL_OK;
   if (store == nullptr || slices == nullptr || (((uintptr_t)store | (uintptr_t)slices) & 15)) return LL_EINVAL;
   const int64_t n_rows = (int64_t)shape->L * shape->C * n_tok;

@@ -230,6 +230,9 @@ __global__ __launch_bounds__(256) void ll_steer_inject_raw_kernel(const uint16_t
   }
 }
 
+// one wavefront per row, four rows per workgroup, and the grid's x extent is a 31-bit number
+constexpr int64_t kMaxInjectRows = (int64_t)4 * 0x7fffffff;
+
 }  // namespace
 
 extern "C" {
@@ -237,6 +240,7 @@ extern "C" {
 int ll_steer_inject_raw(const ll_shape* shape, const void* hidden, const float* v, float alpha, float layer_scale,
                         float clip_ratio, void* out_hidden, void* stream_) {
   if (shape == nullptr || shape->N < 0 || shape->d <= 0 || (shape->d & 7) != 0) return LL_EINVAL;
+  if (shape->N > kMaxInjectRows) return LL_EINVAL;
   if (shape->N == 0) return LL_OK;
   if (hidden == nullptr || v == nullptr || out_hidden == nullptr) return LL_EINVAL;
   const float s = alpha * layer_scale;
@@ -314,6 +318,7 @@ int ll_steer_vector(const void* base, int64_t n_base, const void* target, int64_
 int ll_steer_inject(const ll_shape* shape, const void* hidden, const void* gamma, float eps, const float* v, float alpha,
                     void* out_hidden, void* stream_) {
   if (shape == nullptr || shape->N < 0 || shape->d <= 0 || (shape->d & 7) != 0) return LL_EINVAL;
+  if (shape->N > kMaxInjectRows) return LL_EINVAL;
   if (shape->N == 0) return LL_OK;
   if (hidden == nullptr || gamma == nullptr || v == nullptr || out_hidden == nullptr || !(eps >= 0.f)) return LL_EINVAL;
   if (((uintptr_t)hidden | (uintptr_t)gamma | (uintptr_t)v | (uintptr_t)out_hidden) & 15) return LL_EINVAL;

@@ -174,6 +174,9 @@ def test_inject_raw_and_capture_append_reject_bad_arguments():
     assert L.ll_steer_inject_raw(s, f, f, 1.0, 1.0, float("nan"), f, None) == LL.LL_EINVAL
     assert L.ll_steer_inject_raw(LL.ll_shape(4, 60, 0), f, f, 1.0, 1.0, 0.1, f, None) == LL.LL_EINVAL
     assert L.ll_steer_inject_raw(LL.ll_shape(0, 64, 0), None, None, 1.0, 1.0, 0.1, None, None) == LL.LL_OK
+    too_many = LL.ll_shape(4 * (2 ** 31 - 1) + 1, 64, 0)                          # more rows than the grid can hold
+    assert L.ll_steer_inject_raw(too_many, f, f, 1.0, 1.0, 0.1, f, None) == LL.LL_EINVAL
+    assert L.ll_steer_inject(too_many, f, f, 1e-5, f, 1.0, f, None) == LL.LL_EINVAL
     cs = LL.ll_capture_shape(3, 2, 100, 64)
     assert L.ll_capture_append(None, f, f, 0, 1, None) == LL.LL_EINVAL
     assert L.ll_capture_append(cs, None, f, 0, 1, None) == LL.LL_EINVAL
@@ -186,6 +189,8 @@ def test_inject_raw_and_capture_append_reject_bad_arguments():
     assert L.ll_capture_append(LL.ll_capture_shape(3, 2, 100, 60), f, f, 0, 1, None) == LL.LL_EINVAL
     assert L.ll_capture_append(LL.ll_capture_shape(0, 2, 100, 64), f, f, 0, 1, None) == LL.LL_EINVAL
     assert L.ll_capture_append(cs, None, None, 100, 0, None) == LL.LL_OK         # nothing to append
+    huge = LL.ll_capture_shape(2 ** 31 - 1, 2 ** 31 - 1, 2 ** 40, 64)           # L * C * T leaves 64 bits
+    assert L.ll_capture_append(huge, f, f, 0, 1, None) == LL.LL_EINVAL
 
 
 def test_binding_refuses_cpu_tensors():
