@@ -86,6 +86,7 @@ def main():
     ap.add_argument("--config", default="llama31-70b")
     ap.add_argument("--sample-rows", type=int, default=1024)   # ~12 s of host time on 16 cores
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-vendor-gemm", action="store_true", help="skip the vendor-library GEMM context figure")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -231,6 +232,23 @@ def main():
         result["steer_sweep"] = {"rows": cfg.T, "n_alpha": len(alphas), "sweep_ms": t_sweep, "inject_project_pairs_ms": t_pairs,
                                  "speedup": t_pairs / t_sweep}
         del sww
+    # Context, outside the timed region: the vendor library's plain bf16 GEMM (torch.matmul, i.e. hipBLASLt) on
+    # one row pass of the same shape and the same operand values, with the logits written to HBM and none of the
+    # norm / softmax / top-k work.  Not the product path and not a target: it shows what this box's power and
+    # clocks give a dense bf16 contraction of this shape today.
+    if not args.no_vendor_gemm:
+        rows = min(cfg.chunk_rows, N)
+        a_rows = torch.empty((rows, d), dtype=torch.bfloat16, device=dev)
+        LL.ll_steer_inject(w.hidden.reshape(-1, d)[:rows], w.gamma, cfg.eps, v, 0.0, out=a_rows, stream=stream)
+        logits = torch.empty((rows, V), dtype=torch.bfloat16, device=dev)
+        t_blas = timed_ms(lambda: torch.matmul(a_rows, w.W_U.t(), out=logits), reps=10)
+        del logits, a_rows
+        tf_blas = 2.0 * rows * d * V / (t_blas * 1e-3) / 1e12
+        result["vendor_gemm_context"] = {
+            "what": f"torch.matmul (hipBLASLt) bf16 [{rows},{d}] x [{d},{V}], logits written, no norm/softmax/top-k",
+            "ms": t_blas, "tflops": tf_blas, "frac_bf16_peak": tf_blas / PEAK_BF16_TFLOPS,
+            "this_kernel_over_vendor": tflops / tf_blas,
+        }
     if not args.no_cpu_baseline:
         gpu_np = P.to_numpy(out)
         base_info, rep = cpu_baseline(w, gpu_np, args.sample_rows)
