@@ -208,6 +208,12 @@ def main():
     raw_out = torch.empty_like(big)
     t_raw = timed_ms(lambda: LL.ll_steer_inject_raw(big, v, 2.0, 1.0, 0.1, out=raw_out, stream=stream))
     del store, raw_out
+    # context for the figures above: what a plain device-to-device copy of 1 GiB reaches on this machine
+    cp_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cp_dst = torch.empty_like(cp_src)
+    t_copy = timed_ms(lambda: cp_dst.copy_(cp_src), reps=5)
+    del cp_src, cp_dst
+    result["aux_hbm"]["device_copy_1GiB_GBs"] = 2.0 * (1 << 30) / (t_copy * 1e-3) / 1e9
     result["aux_hbm"].update({
         "capture_append_all_tokens_GBs": 4.0 * N * d / (t_app * 1e-3) / 1e9,
         "capture_append_one_step_us": t_dec * 1e3, "capture_append_one_step_rows": cfg.L,
