@@ -71,6 +71,7 @@ RAGGED = [
     ("lds-k32",        2, 150,  320, 5000, 32, 0),      # 5 K stages, longest top-k list
     ("lds-one-stage",  1, 300,   64, 1500,  5, 0),      # a single K stage per tile
     ("lds-64-splits",  1,  64,  128, 20000, 20, 0),     # one row block: 64 vocabulary splits of one or two tiles
+    ("lds-long-k",     1, 300, 16384, 1000, 10, 4),     # twice the largest paper-shaped hidden size: 256 K stages per tile
 ]
 
 
