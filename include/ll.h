@@ -64,7 +64,8 @@ size_t ll_workspace_bytes(const ll_shape* shape, int k);
  * Requirements: d a positive multiple of 8, V at most 2^31 - 257, 1 <= k <= min(LL_KMAX, V), all
  * tensors 16-byte aligned.  N == 0 is a successful no-op.  Rows are processed in passes of at most 8192 rows
  * so the workspace does not grow with N beyond 4 bytes per row.
- * Arithmetic: bf16 operands, fp32 accumulation and fp32 softmax statistics.
+ * Arithmetic: bf16 operands, fp32 accumulation and fp32 softmax statistics.  A row of `hidden` that
+ * holds NaN or infinity gets NaN statistics and unspecified ids; no other row is affected.
  * Everything is enqueued on `stream`; the call returns without waiting.
  */
 int ll_project(const ll_shape* shape, void* workspace, size_t workspace_bytes,

@@ -132,6 +132,25 @@ def test_zero_rows_are_uniform_and_bad_targets_give_nan():
     P.compare(got, ref, cfg.k, label="zero-rows")
 
 
+def test_a_non_finite_row_leaves_the_other_rows_alone():
+    """Rows are independent: a row holding NaN or infinity must change no other row's result, on either side of a
+    row-block boundary (the rows share workgroups, accumulator tiles and the merge kernel's blocks)."""
+    say("non-finite rows")
+    cfg = WL.LensConfig("nf", L=2, T=200, d=256, V=3000, k=8, n_outliers=2, outlier_scale=20.0)
+    w = WL.make_workload(cfg, DEV, seed=9)
+    clean = run_project(w)
+    h = w.hidden.reshape(-1, cfg.d)
+    bad = {3: float("nan"), 255: float("inf"), 256: float("-inf"), 399: float("nan")}
+    for r, val in bad.items():
+        h[r, 17] = val
+    got = run_project(w)
+    keep = np.array([r for r in range(cfg.N) if r not in bad])
+    for key in ("topk_ids", "topk_p", "target_logp", "entropy"):
+        np.testing.assert_array_equal(got[key][keep], clean[key][keep], err_msg=key)
+    for r in bad:                                   # the row itself: no claim beyond "not a number"
+        assert np.isnan(got["entropy"][r])
+
+
 def test_exact_ties_break_by_ascending_id():
     """Duplicate vocabulary rows give exactly equal logits: the smaller id must come first."""
     say("exact ties")
