@@ -86,6 +86,13 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
   return c;
 }
+// The same with C = 0: the first K half of a vocabulary tile starts its accumulators this way, so
+// that the 256 of them need no clearing between tiles.
+__device__ __forceinline__ f32x4 mfma16_from_zero(bf16x8 a, bf16x8 b) {
+  f32x4 c;
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=a"(c) : "v"(a), "v"(b));
+  return c;
+}
 
 template <class EPI>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
@@ -230,28 +237,29 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   // (Operands come from LDS reads, whose waits the compiler still places; nothing reads an
   // accumulator before the epilogue's own drain.)
 #define LL_MFMA16(a, b, c) mfma16(a, b, c)
-#define LL_ROW(I, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                        \
-  acc[MB + I][0] = LL_MFMA16(fw[I], fah[0], acc[MB + I][0]);                                         \
+#define LL_MFMA16_Z(a, b, c) mfma16_from_zero(a, b)
+#define LL_ROW(MF, I, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                    \
+  acc[MB + I][0] = MF(fw[I], fah[0], acc[MB + I][0]);                                                \
   nw[I] = LL_LDS_FRAG(smem + tW + (NMB + I) * 16 * (DK * 2) + (off));                                \
   LL_SCHED_FENCE();                                                                                  \
-  acc[MB + I][1] = LL_MFMA16(fw[I], fah[1], acc[MB + I][1]);                                         \
+  acc[MB + I][1] = MF(fw[I], fah[1], acc[MB + I][1]);                                                \
   RHOOK(I);                                                                                          \
   LL_SCHED_FENCE();                                                                                  \
-  acc[MB + I][2] = LL_MFMA16(fw[I], fah[2], acc[MB + I][2]);                                         \
+  acc[MB + I][2] = MF(fw[I], fah[2], acc[MB + I][2]);                                                \
   HOOK(I);                                                                                           \
   LL_SCHED_FENCE();                                                                                  \
-  acc[MB + I][3] = LL_MFMA16(fw[I], fah[3], acc[MB + I][3]);                                         \
+  acc[MB + I][3] = MF(fw[I], fah[3], acc[MB + I][3]);                                                \
   LL_SCHED_FENCE();
-#define LL_SLICE(MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                         \
+#define LL_SLICE(MF, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                     \
   LL_SCHED_FENCE();                                                                                  \
-  LL_ROW(0, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(1, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(2, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(3, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(4, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(5, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(6, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(7, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)
+  LL_ROW(MF, 0, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(MF, 1, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(MF, 2, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(MF, 3, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(MF, 4, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(MF, 5, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(MF, 6, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
+  LL_ROW(MF, 7, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)
 
 #define LL_RHOOK_NONE(I) (void)0
   // slice 0 fetches the A fragments of the stage's second K half (the last of A(g) this wavefront
@@ -306,27 +314,26 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   int cW = 0, nW = SLOT_BYTES, nnW = 2 * SLOT_BYTES;
   int cA = W_SLOTS * SLOT_BYTES + a_wave_off, nA = (W_SLOTS + 1) * SLOT_BYTES + a_wave_off;
   for (int tile = tile0; tile < tile1; ++tile) {
-    f32x4 acc[16][4];
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
-
-    for (int kt = 0; kt < KT; ++kt) {
-      LL_SLICE(0, fw0, fa[0], fw1, cW, 8, f_off[0], LL_RHOOK_S0, LL_HOOK_S0)
-      LL_SLICE(8, fw1, fa[0], fw0, cW, 0, f_off[1], LL_RHOOK_NONE, LL_HOOK_S1)
-      LL_SLICE(0, fw0, fa[1], fw1, cW, 8, f_off[1], LL_RHOOK_NONE, LL_HOOK_S2)
-      // stage g+1 landed (W(g+2) and A(g+2) may still be out); all my reads of W(g) are done
-      __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE, 0));
-      __syncthreads();
-      LL_SLICE(8, fw1, fa[1], fw0, nW, 0, f_off[0], LL_RHOOK_S3, LL_HOOK_S3)
+    f32x4 acc[16][4];   // first written by the K half 0 of stage 0, with C = 0
+    // One stage; MF0 is the MFMA form of K half 0: from zero in a tile's first stage, accumulating after.
+#define LL_STAGE(MF0)                                                                       \
+    LL_SLICE(MF0, 0, fw0, fa[0], fw1, cW, 8, f_off[0], LL_RHOOK_S0, LL_HOOK_S0)             \
+    LL_SLICE(MF0, 8, fw1, fa[0], fw0, cW, 0, f_off[1], LL_RHOOK_NONE, LL_HOOK_S1)           \
+    LL_SLICE(LL_MFMA16, 0, fw0, fa[1], fw1, cW, 8, f_off[1], LL_RHOOK_NONE, LL_HOOK_S2)     \
+    /* stage g+1 landed (W(g+2) and A(g+2) may still be out); all my reads of W(g) are done */ \
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE, 0));                         \
+    __syncthreads();                                                                        \
+    LL_SLICE(LL_MFMA16, 8, fw1, fa[1], fw0, nW, 0, f_off[0], LL_RHOOK_S3, LL_HOOK_S3)
+    LL_STAGE(LL_MFMA16_Z)
+    for (int kt = 1; kt < KT; ++kt) {
+      LL_STAGE(LL_MFMA16)
     }
+#undef LL_STAGE
     EPI::tile(acc, st, tile * BM, p);
   }
 #undef LL_SLICE
 #undef LL_ROW
+#undef LL_MFMA16_Z
 #undef LL_MFMA16
 #undef LL_LDS_FRAG
 #undef LL_DMA_TILE
