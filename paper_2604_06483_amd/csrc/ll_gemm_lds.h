@@ -238,17 +238,18 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   // accumulator before the epilogue's own drain.)
 #define LL_MFMA16(a, b, c) mfma16(a, b, c)
 #define LL_MFMA16_Z(a, b, c) mfma16_from_zero(a, b)
+#define LL_J(I, j) (((I) & 1) ? 3 - (j) : (j))   /* row tiles back and forth: one operand changes per MFMA */
 #define LL_ROW(MF, I, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                    \
-  acc[MB + I][0] = MF(fw[I], fah[0], acc[MB + I][0]);                                                \
+  acc[MB + I][LL_J(I, 0)] = MF(fw[I], fah[LL_J(I, 0)], acc[MB + I][LL_J(I, 0)]);                     \
   nw[I] = LL_LDS_FRAG(smem + tW + (NMB + I) * 16 * (DK * 2) + (off));                                \
   LL_SCHED_FENCE();                                                                                  \
-  acc[MB + I][1] = MF(fw[I], fah[1], acc[MB + I][1]);                                                \
+  acc[MB + I][LL_J(I, 1)] = MF(fw[I], fah[LL_J(I, 1)], acc[MB + I][LL_J(I, 1)]);                     \
   RHOOK(I);                                                                                          \
   LL_SCHED_FENCE();                                                                                  \
-  acc[MB + I][2] = MF(fw[I], fah[2], acc[MB + I][2]);                                                \
+  acc[MB + I][LL_J(I, 2)] = MF(fw[I], fah[LL_J(I, 2)], acc[MB + I][LL_J(I, 2)]);                     \
   HOOK(I);                                                                                           \
   LL_SCHED_FENCE();                                                                                  \
-  acc[MB + I][3] = MF(fw[I], fah[3], acc[MB + I][3]);                                                \
+  acc[MB + I][LL_J(I, 3)] = MF(fw[I], fah[LL_J(I, 3)], acc[MB + I][LL_J(I, 3)]);                     \
   LL_SCHED_FENCE();
 #define LL_SLICE(MF, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                     \
   LL_SCHED_FENCE();                                                                                  \
@@ -333,6 +334,7 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   }
 #undef LL_SLICE
 #undef LL_ROW
+#undef LL_J
 #undef LL_MFMA16_Z
 #undef LL_MFMA16
 #undef LL_LDS_FRAG
