@@ -28,19 +28,21 @@ namespace {
 // change hands at a workgroup barrier; of an A tile it reads exactly the rows it loaded itself,
 // so an A slot is the wavefront's own again as soon as its last fragment of the stage is in
 // registers, with no barrier.  That is what the two rings are for: the A fragments of a whole
-// stage are read early (32 registers), and both streams get about two stages between sending a
-// load and needing its data, from the same 160 KB.
+// stage are read one stage early (32 registers), and both streams get about two stages between
+// sending a load and needing its data, from the same 160 KB.
 //
-// Schedule of stage g, four slices of 32 MFMAs: (K half 0, vocabulary tiles 0-7), (0, 8-15),
-// (1, 0-7), (1, 8-15); W fragments alternate between two register sets of eight:
-//   slice 0    : reads the W fragments of slice 1 and the A fragments of K half 1 (the last of
-//                the stage: the wavefront's rows of A(g)'s slot are free); sends the second half
-//                of W(g+2);
-//   slices 1, 2: read the W fragments of the next slice; send A(g+2), half each;
+// Schedule of stage g, four slices of 32 MFMAs: slice S is vocabulary tiles 4 S .. 4 S + 3 in both
+// K halves, the two MFMAs of an accumulator tile back to back (the second takes the first one's
+// result as it leaves the pipe; 1 % on this kernel, 3.5 % on a bare MFMA loop); W fragments
+// alternate between two register sets of eight (four tiles x two halves):
+//   slice 0    : reads the W fragments of slice 1; sends the second half of W(g+2);
+//   slices 1, 2: read the W fragments of the next slice; send A(g+2), half each (into the slot of
+//                A(g), whose fragments all went into registers during stage g-1);
 //   wait + barrier: all loads but the last 16 (W(g+2), A(g+2)) have landed, so stage g+1 is in
 //                LDS for everyone, and everyone holds its last fragments of W(g): that slot is free;
-//   slice 3    : reads the W fragments of slice 0 and the A fragments of K half 0 of stage g+1;
-//                sends the first half of W(g+3) into the slot of W(g).
+//   slice 3    : reads the W fragments of slice 0 of stage g+1 and, row tile by row tile as they
+//                fall dead, all eight A fragments of stage g+1; sends the first half of W(g+3)
+//                into the slot of W(g).
 // Four loads per slice, one behind every eighth MFMA, keep the load pipe evenly fed and the
 // wavefront's issue slots free for the matrix pipe.  The rings are fed unconditionally and run on
 // across vocabulary tiles (the next tile's first stages load under the epilogue); past the last
@@ -216,21 +218,31 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   LL_DMA_W(0); LL_DMA_W(1); LL_DMA_W(2); LL_DMA_W(3);
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE + 4, 15));   // W0 and A0 landed
   __syncthreads();
-  // A: the four row tiles of both K halves of the stage; W: two sets of eight vocabulary tiles of one half
+  // A: the four row tiles of both K halves of the stage.  W: two sets of eight fragments, each the
+  // four vocabulary tiles of a slice in both K halves (fragment 2 t + hk).
   bf16x8 fa[2][4], fw0[8], fw1[8];
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
-    fa[0][j] = *reinterpret_cast<const bf16x8*>(smem + W_SLOTS * SLOT_BYTES + a_wave_off + j * 16 * (DK * 2) + f_off[0]);
+  for (int hk = 0; hk < 2; ++hk)
 #pragma unroll
-  for (int i = 0; i < 8; ++i) fw0[i] = *reinterpret_cast<const bf16x8*>(smem + i * 16 * (DK * 2) + f_off[0]);
+    for (int j = 0; j < 4; ++j)
+      fa[hk][j] = *reinterpret_cast<const bf16x8*>(smem + W_SLOTS * SLOT_BYTES + a_wave_off + j * 16 * (DK * 2) + f_off[hk]);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) fw0[q] = *reinterpret_cast<const bf16x8*>(smem + (q >> 1) * 16 * (DK * 2) + f_off[q & 1]);
 
-  // A stage is four slices of 32 MFMAs: (K half 0, vocabulary tiles 0-7), (0, 8-15), (1, 0-7),
-  // (1, 8-15).  One slice: eight vocabulary tiles (fragments fw) against the four row tiles of a
-  // K half (fah), accumulators MB .. MB+7.  An MFMA runs for 16 cycles, so a gap between two of
-  // them holds at most two or three other instructions: behind the first MFMA of a row of four
-  // goes the LDS read of one W fragment of the next slice (into nw, from LDS offset tW),
-  // behind the second an A fragment read (RHOOK), behind the third a load-to-LDS or a piece of
-  // the streams' bookkeeping (HOOK).  The fences pin that order.
+  // A stage is four slices of 32 MFMAs; slice S is vocabulary tiles 4 S .. 4 S + 3 against the
+  // four row tiles, BOTH K halves: the two MFMAs of an accumulator tile are issued back to back,
+  // the second reading the first one's result.  On this power-limited chip that order is worth
+  // 3.5 % on a bare MFMA loop over the same work with the halves apart (the accumulator goes from
+  // one instruction to the next without a trip through the register file), and it does not stall.
+  // A slice is 16 such pairs.  Slices 1 and 2 walk tile by tile (rows back and forth); slices 0
+  // and 3 walk row tile by row tile, because slice 3 refills the A fragments for the next stage as
+  // it goes: a row tile's two fragments are dead once its four pairs are done, and the next stage's
+  // slice 0 needs them in the same order, 24 MFMAs later at the least.
+  // An MFMA runs for 16 cycles, so a gap between two of them holds at most two or three other
+  // instructions.  Behind the pairs with an even number goes the LDS read of one W fragment of the
+  // next slice (into nw, from the tile at LDS offset tW), behind those with an odd number a
+  // load-to-LDS or a piece of the streams' bookkeeping (HOOK); slice 3's A fragment reads go
+  // between the two MFMAs of a pair (AIN).  The fences pin that order.
 #define LL_LDS_FRAG(ptr) (*reinterpret_cast<const bf16x8*>(ptr))
   // Written as an instruction so that the 64 accumulator tiles stay in AGPRs: given the builtin,
   // the register allocator keeps some of them in VGPRs and copies them in and out around the MFMA.
@@ -238,37 +250,56 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   // accumulator before the epilogue's own drain.)
 #define LL_MFMA16(a, b, c) mfma16(a, b, c)
 #define LL_MFMA16_Z(a, b, c) mfma16_from_zero(a, b)
-#define LL_J(I, j) (((I) & 1) ? 3 - (j) : (j))   /* row tiles back and forth: one operand changes per MFMA */
-#define LL_ROW(MF, I, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                    \
-  acc[MB + I][LL_J(I, 0)] = MF(fw[I], fah[LL_J(I, 0)], acc[MB + I][LL_J(I, 0)]);                     \
-  nw[I] = LL_LDS_FRAG(smem + tW + (NMB + I) * 16 * (DK * 2) + (off));                                \
-  LL_SCHED_FENCE();                                                                                  \
-  acc[MB + I][LL_J(I, 1)] = MF(fw[I], fah[LL_J(I, 1)], acc[MB + I][LL_J(I, 1)]);                     \
-  RHOOK(I);                                                                                          \
-  LL_SCHED_FENCE();                                                                                  \
-  acc[MB + I][LL_J(I, 2)] = MF(fw[I], fah[LL_J(I, 2)], acc[MB + I][LL_J(I, 2)]);                     \
-  HOOK(I);                                                                                           \
-  LL_SCHED_FENCE();                                                                                  \
-  acc[MB + I][LL_J(I, 3)] = MF(fw[I], fah[LL_J(I, 3)], acc[MB + I][LL_J(I, 3)]);                     \
+  // pair P of a slice: vocabulary tile LL_T and row tile LL_J of the slice
+#define LL_SNAKE(outer, inner) (((outer) & 1) ? 3 - (inner) : (inner))
+#define LL_T(JO, P) ((JO) ? LL_SNAKE((P) / 4, (P) % 4) : (P) / 4)
+#define LL_J(JO, P) ((JO) ? (P) / 4 : LL_SNAKE((P) / 4, (P) % 4))
+#define LL_PAIR(MF0, P, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                     \
+  acc[4 * S + LL_T(JO, P)][LL_J(JO, P)] =                                                                            \
+      MF0(fw[2 * LL_T(JO, P)], fa[0][LL_J(JO, P)], acc[4 * S + LL_T(JO, P)][LL_J(JO, P)]);                           \
+  AIN(P);                                                                                                            \
+  LL_SCHED_FENCE();                                                                                                  \
+  acc[4 * S + LL_T(JO, P)][LL_J(JO, P)] =                                                                            \
+      LL_MFMA16(fw[2 * LL_T(JO, P) + 1], fa[1][LL_J(JO, P)], acc[4 * S + LL_T(JO, P)][LL_J(JO, P)]);                 \
+  if ((P) % 2 == 0) {                                                                                                \
+    nw[(P) / 2] = LL_LDS_FRAG(smem + tW + (4 * NS + (P) / 4) * 16 * (DK * 2) + f_off[((P) / 2) & 1]);                \
+  }                                                                                                                  \
+  else {                                                                                                             \
+    HOOK(((P) - 1) / 2);                                                                                             \
+  }                                                                                                                  \
+  AOUT(P);                                                                                                           \
   LL_SCHED_FENCE();
-#define LL_SLICE(MF, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                     \
-  LL_SCHED_FENCE();                                                                                  \
-  LL_ROW(MF, 0, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(MF, 1, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(MF, 2, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(MF, 3, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(MF, 4, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(MF, 5, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(MF, 6, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)                                              \
-  LL_ROW(MF, 7, MB, fw, fah, nw, tW, NMB, off, RHOOK, HOOK)
+#define LL_SLICE(MF0, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                        \
+  LL_SCHED_FENCE();                                                                                                  \
+  LL_PAIR(MF0, 0, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
+  LL_PAIR(MF0, 1, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
+  LL_PAIR(MF0, 2, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
+  LL_PAIR(MF0, 3, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
+  LL_PAIR(MF0, 4, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
+  LL_PAIR(MF0, 5, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
+  LL_PAIR(MF0, 6, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
+  LL_PAIR(MF0, 7, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
+  LL_PAIR(MF0, 8, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
+  LL_PAIR(MF0, 9, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
+  LL_PAIR(MF0, 10, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                           \
+  LL_PAIR(MF0, 11, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                           \
+  LL_PAIR(MF0, 12, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                           \
+  LL_PAIR(MF0, 13, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                           \
+  LL_PAIR(MF0, 14, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                           \
+  LL_PAIR(MF0, 15, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)
 
-#define LL_RHOOK_NONE(I) (void)0
-  // slice 0 fetches the A fragments of the stage's second K half (the last of A(g) this wavefront
-  // needs), slice 3 those of the next stage's first half
-#define LL_RHOOK_S0(I) \
-  if (I < 4) fa[1][I & 3] = LL_LDS_FRAG(smem + cA + (I & 3) * 16 * (DK * 2) + f_off[1])
-#define LL_RHOOK_S3(I) \
-  if (I < 4) fa[0][I & 3] = LL_LDS_FRAG(smem + nA + (I & 3) * 16 * (DK * 2) + f_off[0])
+#define LL_A_NONE(P) (void)0
+  // slice 3 (row tile P / 4 in pairs 4 j .. 4 j + 3): the K half 0 fragment of a row tile is dead
+  // after the first MFMA of its last pair, the K half 1 fragment after the second; both are read
+  // for the next stage from its A tile (the wavefront's own rows), at LDS offset nA
+#define LL_AIN_S3(P)                                                                                   \
+  if ((P) % 4 == 3) fa[0][(P) / 4] = LL_LDS_FRAG(smem + nA + ((P) / 4) * 16 * (DK * 2) + f_off[0]);    \
+  if ((P) % 4 == 0 && (P) > 0) fa[1][((P) / 4 + 3) % 4] = LL_LDS_FRAG(smem + nA + (((P) / 4 + 3) % 4) * 16 * (DK * 2) + f_off[1])
+#define LL_AOUT_S3(P)                                                                                  \
+  if ((P) == 15) {                                                                                     \
+    fa[1][3] = LL_LDS_FRAG(smem + nA + 3 * 16 * (DK * 2) + f_off[1]);                                  \
+    nA = a_flip - nA;   /* LDS reads return in order: the tile read from just now is the wavefront's to refill */ \
+  }
 #define LL_HOOK_S0(I)                                \
   if (I == 0) set_lds_dma_base(w_lds);               \
   if (I == 3) LL_DMA_W(4);                           \
@@ -276,8 +307,8 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   if (I == 5) LL_DMA_W(6);                           \
   if (I == 6) LL_DMA_W(7);                           \
   if (I == 7) advance_w()
-  // (the last A fragments of the stage were read early in slice 0, and LDS reads return in order:
-  // once slice 1 has its first W fragment, A(g)'s slot is the wavefront's own)
+  // (the A fragments of this stage were all read in the previous stage's slice 3: the slot of A(g),
+  // which A(g+2) goes into, has been the wavefront's own since then)
 #define LL_HOOK_S1(I)                                \
   if (I == 3) set_lds_dma_base(a_lds);               \
   if (I == 4) LL_DMA_A(0);                           \
@@ -298,33 +329,29 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
     nnW = nW + SLOT_BYTES >= W_SLOTS * SLOT_BYTES ? 0 : nW + SLOT_BYTES;   \
     LL_PIN_S(nnW);                                   \
   }                                                  \
-  if (I == 6) {                                      \
-    LL_DMA_W(2);                                     \
-    const int t_ = cA;                               \
-    cA = nA;                                         \
-    nA = t_;                                         \
-  }                                                  \
-  if (I == 7) {   /* every row of the slice reads a W fragment from nW: move on after the last */ \
+  if (I == 6) LL_DMA_W(2);                           \
+  if (I == 7) {   /* every even pair of the slice reads a W fragment from nW: move on after the last */ \
     LL_DMA_W(3);                                     \
     cW = nW;                                         \
     nW = nnW;                                        \
   }
 
-  // Consumer state: LDS byte offsets of the W and A tiles of this stage and of the next (the A
-  // offsets include the wavefront's own 64 rows).
+  // Consumer state: LDS byte offsets of the W tiles of this stage and of the next, and of the A
+  // tile the next stage's fragments come from (it includes the wavefront's own 64 rows).
   int cW = 0, nW = SLOT_BYTES, nnW = 2 * SLOT_BYTES;
-  int cA = W_SLOTS * SLOT_BYTES + a_wave_off, nA = (W_SLOTS + 1) * SLOT_BYTES + a_wave_off;
+  int nA = (W_SLOTS + 1) * SLOT_BYTES + a_wave_off;
+  const int a_flip = (2 * W_SLOTS + 1) * SLOT_BYTES + 2 * a_wave_off;   // slot 3 <-> slot 4
   for (int tile = tile0; tile < tile1; ++tile) {
-    f32x4 acc[16][4];   // first written by the K half 0 of stage 0, with C = 0
+    f32x4 acc[16][4];   // first written by the K half 0 MFMAs of stage 0, with C = 0
     // One stage; MF0 is the MFMA form of K half 0: from zero in a tile's first stage, accumulating after.
-#define LL_STAGE(MF0)                                                                       \
-    LL_SLICE(MF0, 0, fw0, fa[0], fw1, cW, 8, f_off[0], LL_RHOOK_S0, LL_HOOK_S0)             \
-    LL_SLICE(MF0, 8, fw1, fa[0], fw0, cW, 0, f_off[1], LL_RHOOK_NONE, LL_HOOK_S1)           \
-    LL_SLICE(LL_MFMA16, 0, fw0, fa[1], fw1, cW, 8, f_off[1], LL_RHOOK_NONE, LL_HOOK_S2)     \
-    /* stage g+1 landed (W(g+2) and A(g+2) may still be out); all my reads of W(g) are done */ \
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE, 0));                         \
-    __syncthreads();                                                                        \
-    LL_SLICE(LL_MFMA16, 8, fw1, fa[1], fw0, nW, 0, f_off[0], LL_RHOOK_S3, LL_HOOK_S3)
+#define LL_STAGE(MF0)                                                                                  \
+    LL_SLICE(MF0, 0, 1, fw0, fw1, cW, 1, LL_A_NONE, LL_A_NONE, LL_HOOK_S0)                             \
+    LL_SLICE(MF0, 1, 0, fw1, fw0, cW, 2, LL_A_NONE, LL_A_NONE, LL_HOOK_S1)                             \
+    LL_SLICE(MF0, 2, 0, fw0, fw1, cW, 3, LL_A_NONE, LL_A_NONE, LL_HOOK_S2)                             \
+    /* stage g+1 landed (W(g+2) and A(g+2) may still be out); all my reads of W(g) are done */         \
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE, 0));                                    \
+    __syncthreads();                                                                                   \
+    LL_SLICE(MF0, 3, 1, fw1, fw0, nW, 0, LL_AIN_S3, LL_AOUT_S3, LL_HOOK_S3)
     LL_STAGE(LL_MFMA16_Z)
     for (int kt = 1; kt < KT; ++kt) {
       LL_STAGE(LL_MFMA16)
@@ -332,17 +359,19 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
 #undef LL_STAGE
     EPI::tile(acc, st, tile * BM, p);
   }
-#undef LL_SLICE
-#undef LL_ROW
+#undef LL_PAIR
+#undef LL_T
 #undef LL_J
+#undef LL_SNAKE
+#undef LL_A_NONE
+#undef LL_AIN_S3
+#undef LL_AOUT_S3
+#undef LL_SLICE
 #undef LL_MFMA16_Z
 #undef LL_MFMA16
 #undef LL_LDS_FRAG
 #undef LL_DMA_TILE
 #undef LL_HOOK_S3
-#undef LL_RHOOK_S3
-#undef LL_RHOOK_S0
-#undef LL_RHOOK_NONE
 #undef LL_PIN_S
 #undef LL_HOOK_S2
 #undef LL_HOOK_S1
