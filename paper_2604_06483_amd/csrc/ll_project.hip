@@ -10,7 +10,9 @@
 
 #include <atomic>
 #include <climits>
+#include <mutex>
 #include <type_traits>
+#include <utility>
 #include <vector>
 
 namespace {
@@ -305,11 +307,12 @@ bool shape_ok(const ll_shape* s, int k) {
 }
 
 Plan make_plan(const ll_shape* s, int k) {
+  const int chunk_rows = CHUNK_ROWS;
   Plan p;
   size_t off = 0;
   p.off_inv_rms = off;
   off = align_up(off + (size_t)s->N * sizeof(float), 256);
-  const size_t rows = (size_t)(s->N < CHUNK_ROWS ? s->N : CHUNK_ROWS);
+  const size_t rows = (size_t)(s->N < chunk_rows ? s->N : chunk_rows);
   p.off_stats = off;
   const size_t partials = rows * MAX_SPLITS < (size_t)MAX_PARTIALS ? rows * MAX_SPLITS : (size_t)MAX_PARTIALS;
   off = align_up(off + partials * sizeof(float4), 256);
@@ -326,10 +329,26 @@ Plan make_plan(const ll_shape* s, int k) {
 // kernel fed from a normalised panel.
 std::atomic<int> g_gemm_path{0};
 
+// A kernel that uses more than 64 KB of dynamic LDS has to be told so once per device; remembered
+// here so that the hot path makes no attribute call.
+int allow_dynamic_lds(const void* kern, size_t lds) {
+  static std::mutex mu;
+  static std::vector<std::pair<int, const void*>> done;
+  int dev = -1;
+  LL_HIP_CHECK(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> lock(mu);
+  for (const auto& e : done)
+    if (e.first == dev && e.second == kern) return LL_OK;
+  LL_HIP_CHECK(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  done.emplace_back(dev, kern);
+  return LL_OK;
+}
+
 int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
                  const void* W_U, const float* bias, unsigned flags, float eps, int k, const int32_t* target_ids,
                  int32_t* out_topk_ids, float* out_topk_p,
                  float* out_target_logp, float* out_entropy, hipStream_t stream, float* phase_ms) {
+  const int chunk_rows = CHUNK_ROWS;
   if (!shape_ok(shape, k)) return LL_EINVAL;
   if (shape->N == 0) {
     if (phase_ms) phase_ms[0] = phase_ms[1] = phase_ms[2] = 0.f;
@@ -373,7 +392,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   else
     kern = LL_PICK(32);
 #undef LL_PICK
-  LL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  if (const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds); rc != LL_OK) return rc;
   // The direct-to-LDS kernel reads hidden in place when the rows need neither scaling nor padding.
   const bool need_panel = dma && (has_gamma || plan.lda != d);
 
@@ -399,8 +418,8 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   } while (0)
 
   const int tiles = (V + BM - 1) / BM;
-  for (int64_t r0 = 0; r0 < N; r0 += CHUNK_ROWS) {
-    const int rows = (int)((N - r0) < CHUNK_ROWS ? (N - r0) : CHUNK_ROWS);
+  for (int64_t r0 = 0; r0 < N; r0 += chunk_rows) {
+    const int rows = (int)((N - r0) < chunk_rows ? (N - r0) : chunk_rows);
     const uint16_t* h_rows = static_cast<const uint16_t*>(hidden) + r0 * d;
     // a2 (+ a3 when the panel is used)
     LL_CHECK_F(mark());
@@ -546,7 +565,7 @@ int sweep_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, c
   LL_CHECK_S(hipGetLastError());
   auto kern = ll_lens_gemm_dma_kernel<SweepEpilogue>;
   const size_t lds = (size_t)SLOTS * SLOT_BYTES;
-  LL_CHECK_S(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  if (const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds); rc != LL_OK) return rc;
 
   for (int64_t r0 = 0; r0 < N; r0 += CHUNK_ROWS) {
     const int rows = (int)((N - r0 < CHUNK_ROWS) ? (N - r0) : CHUNK_ROWS);
