@@ -24,6 +24,7 @@ extern "C" {
 #define LL_EINVAL      -1   /* null required pointer, bad size, k out of range, d not a multiple of 8 */
 #define LL_EWORKSPACE  -2   /* workspace missing or smaller than ll_workspace_bytes()              */
 #define LL_EHIP        -3   /* a HIP call failed; ll_last_hip_error() gives its code                */
+#define LL_ESCRATCH    -4   /* ll_project_static: the shape does not fit the library's static buffer  */
 
 #define LL_KMAX         32  /* largest supported top-k */
 
@@ -105,6 +106,37 @@ int ll_project_timed(const ll_shape* shape, void* workspace, size_t workspace_by
                      int32_t* out_topk_ids, float* out_topk_p,
                      float* out_target_logp, float* out_entropy,
                      void* stream, float* phase_ms);
+
+/*
+ * ll_project for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops (e.g. the lens of the newest token after every decoding
+ * step), harnesses that forbid hipMalloc.  Same arguments, results and kernels as ll_project,
+ * minus the workspace: the partial results and the normalised panel live in a device array inside
+ * this library, LL_STATIC_SCRATCH_BYTES large, which every GPU the library runs on holds until the
+ * process ends.  The call allocates and frees nothing.
+ *
+ * Rows are processed in passes of ll_project_static_pass_rows(shape, k) rows: 8192 as in
+ * ll_project when that plan fits the buffer (then the results are bit-identical to ll_project's),
+ * otherwise the largest multiple of 256 that fits (same quantities; the fp32 partial sums of a row
+ * are then merged from a different number of vocabulary splits).  LL_ESCRATCH if not even 256 rows
+ * fit (d above roughly 100 000).
+ *
+ * All calls on one GPU share that GPU's buffer: two calls whose kernels may overlap on the same
+ * GPU (different streams, different threads) race; calls queued on one stream are safe.  The
+ * buffer keeps the last call's contents and nothing in it needs clearing.  The first call on a
+ * device looks up the buffer's address (no allocation) and sets a kernel attribute: make it
+ * outside stream capture.
+ */
+#define LL_STATIC_SCRATCH_BYTES (64u << 20)
+int ll_project_static(const ll_shape* shape,
+                      const void* hidden, const void* gamma, const void* W_U,
+                      float eps, int k, const int32_t* target_ids,
+                      int32_t* out_topk_ids, float* out_topk_p,
+                      float* out_target_logp, float* out_entropy,
+                      void* stream);
+/* Rows per pass ll_project_static uses for this shape and k (pure host arithmetic); 0 if the
+ * shape is invalid or does not fit. */
+int64_t ll_project_static_pass_rows(const ll_shape* shape, int k);
 
 /*
  * Steering direction (paper Sec. 3.4, Eq. 2): v = (y+ - y-) / ||y+ - y-||_2 with y+ the mean

@@ -12,8 +12,9 @@ from ctypes import POINTER, Structure, c_char_p, c_float, c_int, c_int32, c_int6
 
 import torch
 
-LL_OK, LL_EINVAL, LL_EWORKSPACE, LL_EHIP = 0, -1, -2, -3
+LL_OK, LL_EINVAL, LL_EWORKSPACE, LL_EHIP, LL_ESCRATCH = 0, -1, -2, -3, -4
 LL_KMAX = 32
+LL_STATIC_SCRATCH_BYTES = 64 << 20
 LL_FLAG_TOPK_SOFTMAX = 1
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libll.so")
@@ -56,6 +57,10 @@ def lib() -> ctypes.CDLL:
         L.ll_project_ex.restype = c_int
         L.ll_project_timed.argtypes = _PROJECT_ARGS + [POINTER(c_float)]
         L.ll_project_timed.restype = c_int
+        L.ll_project_static.argtypes = _PROJECT_ARGS[:1] + _PROJECT_ARGS[3:]
+        L.ll_project_static.restype = c_int
+        L.ll_project_static_pass_rows.argtypes = [POINTER(ll_shape), c_int]
+        L.ll_project_static_pass_rows.restype = c_int64
         L.ll_steer_workspace_bytes.argtypes = [c_int32]
         L.ll_steer_workspace_bytes.restype = c_size_t
         L.ll_steer_vector.argtypes = [c_void_p, c_int64, c_void_p, c_int64, c_int32, c_int, c_void_p,
@@ -175,6 +180,39 @@ def ll_project(hidden, gamma, W_U, eps, k, target_ids=None, *, workspace=None, s
     rc = lib().ll_project(*args)
     if rc != LL_OK:
         raise LLError(rc, "ll_project")
+    return ids, p, logp, ent
+
+
+def ll_project_static_pass_rows(N: int, d: int, V: int, k: int) -> int:
+    return int(lib().ll_project_static_pass_rows(ll_shape(N, d, V), k))
+
+
+def ll_project_static(hidden, gamma, W_U, eps, k, target_ids=None, *, stream=None, out=None):
+    """ll_project without a workspace: the library's own static device buffer holds the partial results, and the
+    call allocates nothing (pass `out` to keep this wrapper from allocating the result tensors).  Calls that may
+    overlap on one GPU race on that buffer.  Same results as ll_project."""
+    d = hidden.shape[-1]
+    h2 = hidden.reshape(-1, d)
+    N = h2.shape[0]
+    V = W_U.shape[0]
+    _check(h2, torch.bfloat16, "hidden")
+    _check(W_U, torch.bfloat16, "W_U", (V, d))
+    if gamma is not None:
+        _check(gamma, torch.bfloat16, "gamma", (d,))
+    if target_ids is not None:
+        _check(target_ids, torch.int32, "target_ids", (N,))
+    dev = hidden.device
+    if out is None:
+        ids = torch.empty((N, k), dtype=torch.int32, device=dev)
+        p = torch.empty((N, k), dtype=torch.float32, device=dev)
+        logp = torch.empty((N,), dtype=torch.float32, device=dev) if target_ids is not None else None
+        ent = torch.empty((N,), dtype=torch.float32, device=dev)
+    else:
+        ids, p, logp, ent = out
+    rc = lib().ll_project_static(ll_shape(N, d, V), _ptr(h2), _ptr(gamma), _ptr(W_U), float(eps), int(k), _ptr(target_ids),
+                                 _ptr(ids), _ptr(p), _ptr(logp), _ptr(ent), _stream(stream))
+    if rc != LL_OK:
+        raise LLError(rc, "ll_project_static")
     return ids, p, logp, ent
 
 

@@ -21,6 +21,7 @@ const char* ll_error_string(int code) {
     case LL_EINVAL: return "invalid argument (null pointer, bad size or alignment, k out of range, d not a multiple of 8)";
     case LL_EWORKSPACE: return "workspace missing, misaligned or smaller than required";
     case LL_EHIP: return "a HIP call failed (see ll_last_hip_error)";
+    case LL_ESCRATCH: return "the shape needs more than the library's static scratch buffer holds (use ll_project with a workspace)";
     default: return "unknown error code";
   }
 }

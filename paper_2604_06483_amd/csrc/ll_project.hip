@@ -306,8 +306,7 @@ bool shape_ok(const ll_shape* s, int k) {
   return true;
 }
 
-Plan make_plan(const ll_shape* s, int k) {
-  const int chunk_rows = CHUNK_ROWS;
+Plan make_plan(const ll_shape* s, int k, int chunk_rows = CHUNK_ROWS) {
   Plan p;
   size_t off = 0;
   p.off_inv_rms = off;
@@ -347,8 +346,8 @@ int allow_dynamic_lds(const void* kern, size_t lds) {
 int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
                  const void* W_U, const float* bias, unsigned flags, float eps, int k, const int32_t* target_ids,
                  int32_t* out_topk_ids, float* out_topk_p,
-                 float* out_target_logp, float* out_entropy, hipStream_t stream, float* phase_ms) {
-  const int chunk_rows = CHUNK_ROWS;
+                 float* out_target_logp, float* out_entropy, hipStream_t stream, float* phase_ms,
+                 int chunk_rows = CHUNK_ROWS) {
   if (!shape_ok(shape, k)) return LL_EINVAL;
   if (shape->N == 0) {
     if (phase_ms) phase_ms[0] = phase_ms[1] = phase_ms[2] = 0.f;
@@ -361,7 +360,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   if ((flags & ~(unsigned)LL_FLAG_TOPK_SOFTMAX) != 0 || ((uintptr_t)bias & 3)) return LL_EINVAL;
   const uintptr_t align_or = (uintptr_t)hidden | (uintptr_t)W_U | (uintptr_t)gamma;
   if (align_or & 15) return LL_EINVAL;
-  const Plan plan = make_plan(shape, k);
+  const Plan plan = make_plan(shape, k, chunk_rows);
   if (workspace == nullptr || workspace_bytes < plan.total || ((uintptr_t)workspace & 255)) return LL_EWORKSPACE;
 
   unsigned char* ws = static_cast<unsigned char*>(workspace);
@@ -615,9 +614,61 @@ int sweep_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, c
   return LL_OK;
 }
 
+// ---------------------------------------------------------------------------------------
+// Allocation-free variant: the workspace of ll_project in a device array of this library, for
+// callers that cannot allocate.  The array's name is a host-side handle, not a device address:
+// its address on the current device is looked up once per device and only that pointer is used
+// from then on.  Nothing in the workspace has to start at zero (inv_rms, the partials and the
+// panel are each written in full before they are read), so stale contents of an earlier call do
+// not matter.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char ll_static_scratch[LL_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+std::atomic<void*> g_static_scratch_ptr[MAX_DEVICES];
+
+int static_scratch_of_current_device(void** out) {
+  int dev = -1;
+  LL_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return LL_EINVAL;
+  void* ptr = g_static_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {
+    LL_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(ll_static_scratch)));
+    if (ptr == nullptr || ((uintptr_t)ptr & 255)) return LL_EHIP;
+    g_static_scratch_ptr[dev].store(ptr, std::memory_order_release);   // the same address whoever gets here first
+  }
+  *out = ptr;
+  return LL_OK;
+}
+
+// Rows per pass for the static buffer: the usual 8192 when the plan fits, else the largest
+// multiple of the row block that does; 0 when not even one row block fits.
+int static_chunk_rows(const ll_shape* s, int k) {
+  for (int rows = CHUNK_ROWS; rows >= BN; rows -= BN)
+    if (make_plan(s, k, rows).total <= (size_t)LL_STATIC_SCRATCH_BYTES) return rows;
+  return 0;
+}
+
 }  // namespace
 
 extern "C" {
+
+int ll_project_static(const ll_shape* shape, const void* hidden, const void* gamma, const void* W_U, float eps, int k,
+                      const int32_t* target_ids, int32_t* out_topk_ids, float* out_topk_p, float* out_target_logp,
+                      float* out_entropy, void* stream) {
+  if (!shape_ok(shape, k)) return LL_EINVAL;
+  if (shape->N == 0) return LL_OK;
+  const int chunk = static_chunk_rows(shape, k);
+  if (chunk == 0) return LL_ESCRATCH;
+  void* ws = nullptr;
+  if (const int rc = static_scratch_of_current_device(&ws); rc != LL_OK) return rc;
+  return project_impl(shape, ws, (size_t)LL_STATIC_SCRATCH_BYTES, hidden, gamma, W_U, nullptr, 0u, eps, k, target_ids,
+                      out_topk_ids, out_topk_p, out_target_logp, out_entropy, static_cast<hipStream_t>(stream), nullptr, chunk);
+}
+
+int64_t ll_project_static_pass_rows(const ll_shape* shape, int k) {
+  if (!shape_ok(shape, k)) return 0;
+  return static_chunk_rows(shape, k);
+}
 
 size_t ll_steer_sweep_workspace_bytes(const ll_shape* shape, int n_alpha) {
   if (!sweep_shape_ok(shape, n_alpha)) return 0;

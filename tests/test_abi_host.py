@@ -29,15 +29,17 @@ def test_library_exports_every_declared_symbol():
 
 def test_header_constants_match_binding():
     text = open(HEADER).read()
-    for name in ("LL_OK", "LL_EINVAL", "LL_EWORKSPACE", "LL_EHIP", "LL_KMAX"):
+    for name in ("LL_OK", "LL_EINVAL", "LL_EWORKSPACE", "LL_EHIP", "LL_ESCRATCH", "LL_KMAX"):
         m = re.search(rf"#define\s+{name}\s+(-?\d+)", text)
         assert m and int(m.group(1)) == getattr(LL, name)
+    m = re.search(r"#define\s+LL_STATIC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", text)
+    assert m and int(m.group(1)) << int(m.group(2)) == LL.LL_STATIC_SCRATCH_BYTES
 
 
 def test_error_strings():
     L = LL.lib()
-    seen = {L.ll_error_string(c) for c in (0, -1, -2, -3)}
-    assert len(seen) == 4 and all(s for s in seen)
+    seen = {L.ll_error_string(c) for c in (0, -1, -2, -3, -4)}
+    assert len(seen) == 5 and all(s for s in seen)
     assert L.ll_error_string(-99) == b"unknown error code"
     assert L.ll_last_hip_error() == 0
 
@@ -103,6 +105,36 @@ def test_project_rejects_bad_arguments_without_touching_the_gpu():
     a = ok
     assert L.ll_project_timed(a["shape"], a["ws"], a["wsb"], a["h"], a["g"], a["w"], a["eps"], a["k"], a["t"],
                               a["ids"], a["p"], a["lp"], a["e"], a["st"], None) == LL.LL_EINVAL
+
+
+def test_static_variant_sizes_its_passes_and_rejects_what_does_not_fit():
+    """ll_project_static: pass size from host arithmetic; bad arguments and oversized shapes are refused before
+    anything touches the device (fake pointers, no GPU)."""
+    L = LL.lib()
+    f = _fake()
+    # the usual pass when the plan fits the static buffer
+    assert LL.ll_project_static_pass_rows(700, 256, 5000, 10) == 8192
+    assert LL.ll_workspace_bytes(8192, 256, 5000, 10) <= LL.LL_STATIC_SCRATCH_BYTES
+    # d = 8192, k = 20: the 8192-row plan is larger than the buffer, a smaller multiple of 256 is used
+    assert LL.ll_workspace_bytes(8192, 8192, 128256, 20) > LL.LL_STATIC_SCRATCH_BYTES
+    rows = LL.ll_project_static_pass_rows(121500, 8192, 128256, 20)
+    assert 256 <= rows < 8192 and rows % 256 == 0
+    assert LL.ll_workspace_bytes(rows, 8192, 128256, 20) <= LL.LL_STATIC_SCRATCH_BYTES + 121500 * 4
+    assert LL.ll_project_static_pass_rows(81, 8192, 128256, 20) > 0          # one decoding step's rows always fit
+    # invalid shape or k: 0 rows, LL_EINVAL
+    assert LL.ll_project_static_pass_rows(10, 60, 100, 5) == 0
+    assert LL.ll_project_static_pass_rows(10, 64, 100, 0) == 0
+    call = lambda shape, k=4, h=f, w=f, ids=f: L.ll_project_static(shape, h, f, w, 1e-5, k, f, ids, f, f, f, None)
+    assert call(LL.ll_shape(16, 60, 300)) == LL.LL_EINVAL
+    assert call(LL.ll_shape(16, 64, 300), k=0) == LL.LL_EINVAL
+    assert call(None) == LL.LL_EINVAL
+    assert call(LL.ll_shape(0, 64, 300), h=None, w=None, ids=None) == LL.LL_OK
+    # not even one row block fits: refused with its own code
+    big = LL.ll_shape(1000, 1 << 18, 300)
+    assert LL.ll_project_static_pass_rows(1000, 1 << 18, 300, 4) == 0
+    assert LL.ll_project_static_pass_rows(16, 1 << 18, 300, 4) > 0            # a handful of such rows does fit
+    assert call(big) == LL.LL_ESCRATCH
+    assert b"static" in L.ll_error_string(LL.LL_ESCRATCH)
 
 
 def test_project_ex_rejects_unknown_flags_and_misaligned_bias():
