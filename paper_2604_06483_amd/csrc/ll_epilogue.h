@@ -44,13 +44,15 @@ constexpr float LOG2E = 1.4426950408889634f;
 // ---------------------------------------------------------------------------------------
 #define LL_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+typedef const float __attribute__((address_space(4)))* const_f32_ptr;   // read through scalar loads when the address is wave-uniform
+
 struct GemmArgs {
   const uint16_t* A;        // [rows, lda] bf16 (this pass's rows)
   const float* inv_rms;     // [rows] or nullptr (rows already normalised)
   const uint16_t* gamma;    // [d] or nullptr
   const uint16_t* W;        // [V, d] bf16
   const int32_t* target;    // [rows] or nullptr
-  const float* bias;        // [V] fp32 or nullptr: the b of Eq. 1
+  const float* bias;        // [tiles * BM] fp32 (zero padded beyond V) or nullptr: the b of Eq. 1
   float4* stats;            // [rows, splits]     (m, S, T, z_target)
   uint2* top;               // [rows, splits, k]  (logit bits, id), sorted
   int64_t lda;              // row stride of A in elements
@@ -217,10 +219,13 @@ __device__ __forceinline__ void epilogue_group(const ACC& acc, RowState<KR>& st,
   float x[32];
   load_group<I>(acc, x);
   const int g0 = v0 + 32 * I;
-  if (BIAS) {   // one coalesced load of the group's 32 biases, then a broadcast per entry
-    const unsigned b = __float_as_uint(bias[min(g0 + (int)(threadIdx.x & 31), V - 1)]);
+  if (BIAS) {
+    // The b of Eq. 1: the same 32 values for every lane, from a copy of the bias that is padded
+    // to whole tiles.  Wave-uniform addresses through the constant address space: scalar loads,
+    // which do not count against the vector-memory counter the operand rings are waited on.
+    const_f32_ptr b = (const_f32_ptr)(uintptr_t)(bias + g0);
 #pragma unroll
-    for (int o = 0; o < 32; ++o) x[o] += __uint_as_float(__builtin_amdgcn_readlane(b, o));
+    for (int o = 0; o < 32; ++o) x[o] += b[o];
   }
   if (partial) {   // only the last tile of the vocabulary: a real branch (the empty asm keeps it one)
     asm volatile("");
@@ -321,8 +326,8 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs& p, const RowState
 
 // What a GEMM kernel does with a finished tile is a policy: the state of the lane's row, how a
 // tile updates it, and what goes to the workspace at the end of the sweep.
-template <int KR>
-struct TopKEpilogue {   // a5..a7: softmax statistics, k best logits, target logit
+template <int KR, bool BIAS = false>
+struct TopKEpilogue {   // a5..a7: softmax statistics, k best logits, target logit (BIAS: Eq. 1's b added to every logit first)
   using State = RowState<KR>;
   static __device__ __forceinline__ void init(State& st, const GemmArgs& p, int my_row) {
     st.init();
@@ -330,7 +335,7 @@ struct TopKEpilogue {   // a5..a7: softmax statistics, k best logits, target log
   }
   template <class ACC>
   static __device__ __forceinline__ void tile(const ACC& acc, State& st, int v0, const GemmArgs& p) {
-    epilogue_tile<KR, false, ACC>(acc, st, v0, p.V, nullptr);
+    epilogue_tile<KR, BIAS, ACC>(acc, st, v0, p.V, p.bias);
   }
   static __device__ __forceinline__ void store(const GemmArgs& p, const State& st, int my_row, int split) {
     epilogue_store(p, st, my_row, split);
@@ -344,7 +349,6 @@ struct TopKEpilogue {   // a5..a7: softmax statistics, k best logits, target log
 // constant address space (wave-uniform addresses: scalar loads, one SGPR operand per add).
 // ---------------------------------------------------------------------------------------
 constexpr int SWEEP_MAX = LL_SWEEP_MAX;
-typedef const float __attribute__((address_space(4)))* const_f32_ptr;
 
 struct SweepState {
   float m[SWEEP_MAX], s[SWEEP_MAX], t[SWEEP_MAX];

@@ -93,6 +93,14 @@ __global__ __launch_bounds__(256) void ll_norm_panel_kernel(const uint16_t* __re
   for (int c = n16 + lane; c < n16_pad; c += 64) dst[c] = make_uint4(0, 0, 0, 0);
 }
 
+// Copy of the bias of Eq. 1 padded with zeros to whole vocabulary tiles, so that the epilogue
+// reads 32 entries per group without looking at V.
+__global__ __launch_bounds__(256) void ll_pad_bias_kernel(const float* __restrict__ bias, int V, float* __restrict__ padded,
+                                                          int n_padded) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_padded; i += gridDim.x * blockDim.x)
+    padded[i] = i < V ? bias[i] : 0.f;
+}
+
 __global__ __launch_bounds__(256) void ll_fill_f32_kernel(float* __restrict__ p, int n, float value) {
   for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = value;
 }
@@ -293,7 +301,7 @@ __global__ __launch_bounds__(256) void ll_sweep_merge_kernel(const float4* __res
 // host side
 // ---------------------------------------------------------------------------------------
 struct Plan {
-  size_t off_inv_rms, off_stats, off_top, off_panel, total;
+  size_t off_inv_rms, off_bias, off_stats, off_top, off_panel, total;
   int64_t lda;
 };
 
@@ -311,6 +319,8 @@ Plan make_plan(const ll_shape* s, int k, int chunk_rows = CHUNK_ROWS) {
   size_t off = 0;
   p.off_inv_rms = off;
   off = align_up(off + (size_t)s->N * sizeof(float), 256);
+  p.off_bias = off;   // the bias padded to whole tiles (ll_project_ex)
+  off = align_up(off + (size_t)((s->V + BM - 1) / BM) * BM * sizeof(float), 256);
   const size_t rows = (size_t)(s->N < chunk_rows ? s->N : chunk_rows);
   p.off_stats = off;
   const size_t partials = rows * MAX_SPLITS < (size_t)MAX_PARTIALS ? rows * MAX_SPLITS : (size_t)MAX_PARTIALS;
@@ -374,14 +384,15 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   const bool has_gamma = gamma != nullptr;
   // The direct-to-LDS kernel addresses rows with 32-bit byte offsets from a per-tile base.
   const bool dma_ok = d % DK == 0 && (int64_t)BM * d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * plan.lda * 2 < (int64_t)1 << 31;
-  // A bias (rare: the paper's model families have none) goes through the register-staged kernel,
-  // so that the fast kernel carries no code or registers for it.
-  const bool dma = g_gemm_path.load(std::memory_order_relaxed) != 1 && dma_ok && bias == nullptr;
+  // A bias (rare: the paper's model families have none) selects a separate instantiation of the
+  // kernel, so that calls without one carry no code or registers for it.
+  const bool dma = g_gemm_path.load(std::memory_order_relaxed) != 1 && dma_ok;
   const size_t lds = dma ? (size_t)SLOTS * SLOT_BYTES : (size_t)(BM + BN) * BK * 2;
   // The top-k lists live in registers: the kernels are built for a few list lengths KR >= k.
   void (*kern)(const GemmArgs);
 #define LL_PICK(KR) \
-  (dma ? ll_lens_gemm_dma_kernel<TopKEpilogue<KR>> : (bias ? ll_lens_gemm_kernel<KR, true> : ll_lens_gemm_kernel<KR, false>))
+  (dma ? (bias ? ll_lens_gemm_dma_kernel<TopKEpilogue<KR, true>> : ll_lens_gemm_dma_kernel<TopKEpilogue<KR, false>>) \
+       : (bias ? ll_lens_gemm_kernel<KR, true> : ll_lens_gemm_kernel<KR, false>))
   if (k <= 4)
     kern = LL_PICK(4);
   else if (k <= 12)
@@ -417,6 +428,12 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   } while (0)
 
   const int tiles = (V + BM - 1) / BM;
+  float* bias_padded = nullptr;
+  if (bias != nullptr) {
+    bias_padded = reinterpret_cast<float*>(ws + plan.off_bias);
+    hipLaunchKernelGGL(ll_pad_bias_kernel, dim3((tiles * BM + 1023) / 1024), dim3(256), 0, stream, bias, V, bias_padded, tiles * BM);
+    LL_CHECK_F(hipGetLastError());
+  }
   for (int64_t r0 = 0; r0 < N; r0 += chunk_rows) {
     const int rows = (int)((N - r0) < chunk_rows ? (N - r0) : chunk_rows);
     const uint16_t* h_rows = static_cast<const uint16_t*>(hidden) + r0 * d;
@@ -449,7 +466,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     a.gamma = static_cast<const uint16_t*>(gamma);
     a.W = static_cast<const uint16_t*>(W_U);
     a.target = target_ids ? target_ids + r0 : nullptr;
-    a.bias = bias;
+    a.bias = bias_padded;
     a.stats = stats;
     a.top = top;
     a.rows = rows;

@@ -10,3 +10,25 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs an MI355X (runs the HIP library)")
+
+
+_CONFIG = None
+
+
+@pytest.hookimpl(trylast=True)
+def pytest_sessionstart(session):
+    global _CONFIG
+    _CONFIG = session.config
+
+
+def say(msg):
+    """One line that names the GPU case about to run (test, shape, entry point) or reports what it measured,
+    written past pytest's output capture and flushed, so that it is on the terminal before the GPU step starts."""
+    line = f"[gpu-case] {msg}"
+    tr = _CONFIG.pluginmanager.get_plugin("terminalreporter") if _CONFIG is not None else None
+    if tr is not None:
+        tr.ensure_newline()
+        tr.write_line(line)
+        tr._tw.flush()
+    else:
+        print(line, file=sys.stderr, flush=True)

@@ -1,8 +1,16 @@
 """Comparison of the HIP library's results with the CPU oracle, to the stated bar:
 
-    |d target_logp| <= 2e-3, |d entropy| <= 2e-3 nats, top-k probabilities within 1e-3,
-    top-k ids identical except where the oracle's own logits are closer than 1e-3
-    (several orders are then correct: the id the library put there must be a near-tie).
+    |d target_logp| <= 2e-3, |d entropy| <= 2e-3 nats, top-k probabilities within 1e-3 absolute
+    AND within 2e-3 in the log domain (at vocabulary sizes of 1e5 the probabilities themselves are
+    about 1e-3, where the absolute gate says little; the log gate is the log-prob tolerance applied
+    to the listed tokens), top-k ids identical except where the oracle's own logits are closer than
+    1e-3 (several orders are then correct: the id the library put there must be a near-tie).
+
+Which oracle is the gate.  The contraction's inputs are bf16: the gate is the oracle that rounds
+the normalised row to bf16 once (round-to-nearest-even, straight from fp64) before the product
+with W_U, as the kernels do.  The oracle without that rounding is the un-rounded reference: the
+library's deviation from it is REPORTED (`deviation_from_unrounded`), never gated; the rounding
+alone moves a logit by about 3e-5 sqrt(d), more than the tolerances at the larger hidden sizes.
 
 The oracle gets the same bf16 bit patterns the GPU got, copied to the host.
 """
@@ -13,7 +21,12 @@ import oracle.lens_oracle as O
 TOL_LOGP = 2e-3
 TOL_ENT = 2e-3
 TOL_P = 1e-3
+TOL_LOG_P = 2e-3      # |d log p_i| of the listed tokens
 TIE_BAND = 1e-3
+P_FLOOR = 1e-30       # below this an fp32 probability is (nearly) denormal: no log-domain claim
+
+R1_STATEMENT = ("gate: oracle with the normalised row rounded once to bf16 (the contraction's inputs are bf16); "
+                "the deviation from the un-rounded fp64 oracle is reported, not gated")
 
 
 def oracle_rows(hidden_bits, gamma_bits, w_bits, eps, k, target_ids, round_a=True, bias=None):
@@ -41,15 +54,28 @@ def compare(gpu, ref, k, has_target=True, label=""):
         report["max_logp_err"] = float(lp_err.max()) if lp_err.size else 0.0
         assert report["max_logp_err"] <= TOL_LOGP, f"{label}: target_logp off by {report['max_logp_err']:.3e}"
     # probabilities, position by position (the sorted probabilities are unique even when ids are not)
-    p_err = np.abs(gpu["topk_p"].astype(np.float64) - ref["topk_p"])
+    p_gpu = gpu["topk_p"].astype(np.float64)
+    p_err = np.abs(p_gpu - ref["topk_p"])
     report["max_p_err"] = float(p_err.max())
     assert p_err.max() <= TOL_P, f"{label}: top-k probability off by {p_err.max():.3e}"
-    # ids
-    gid = gpu["topk_ids"].astype(np.int64)
+    big = ref["topk_p"] > P_FLOOR
+    assert np.all(p_gpu[big] > 0.0), f"{label}: a listed probability underflowed"
+    lp_err = np.abs(np.log(p_gpu[big]) - np.log(ref["topk_p"][big]))
+    report["max_log_p_err"] = float(lp_err.max(initial=0.0))
+    assert report["max_log_p_err"] <= TOL_LOG_P, f"{label}: log of a top-k probability off by {report['max_log_p_err']:.3e}"
+    report.update(validate_ids(gpu["topk_ids"], ref, label))
+    return report
+
+
+def validate_ids(gpu_ids, ref, label=""):
+    """Ids equal the oracle's, except where the oracle's own logits are closer than TIE_BAND: there the id the
+    library listed at a rank must carry a logit within TIE_BAND of the oracle's logit at that rank.  Ids in range
+    and distinct within a row.  ref needs z [R, V], topk_ids and topk_logits [R, k]."""
+    V = ref["z"].shape[1]
+    gid = np.asarray(gpu_ids).astype(np.int64)
+    assert gid.shape == ref["topk_ids"].shape, f"{label}: id array shape"
     assert gid.min() >= 0 and gid.max() < V, f"{label}: id out of range"
     mism = gid != ref["topk_ids"]
-    report["id_mismatches"] = int(mism.sum())
-    report["id_positions"] = int(mism.size)
     rows, pos = np.nonzero(mism)
     for r, i in zip(rows, pos):
         z_here = ref["topk_logits"][r, i]
@@ -57,10 +83,32 @@ def compare(gpu, ref, k, has_target=True, label=""):
         assert abs(z_gpu_choice - z_here) < TIE_BAND, (
             f"{label}: row {r} rank {i}: id {gid[r, i]} (oracle logit {z_gpu_choice:.6f}) is not a near-tie of "
             f"oracle id {ref['topk_ids'][r, i]} (logit {z_here:.6f})")
-    # each row's ids are distinct
-    srt = np.sort(gid, axis=1)
-    assert np.all(srt[:, 1:] != srt[:, :-1]) if k > 1 else True, f"{label}: duplicate ids in a row"
-    return report
+    if gid.shape[1] > 1:
+        srt = np.sort(gid, axis=1)
+        assert np.all(srt[:, 1:] != srt[:, :-1]), f"{label}: duplicate ids in a row"
+    return {"id_mismatches": int(mism.sum()), "id_positions": int(mism.size)}
+
+
+def deviation_from_unrounded(gpu, ref_unrounded, has_target=True):
+    """REPORT, not a gate: how far the library's results are from the oracle that does NOT round the normalised
+    row to bf16 (fp64 throughout).  Maximum and standard deviation per logit-derived quantity."""
+    rep = {"statement": R1_STATEMENT}
+
+    def put(name, diff):
+        diff = np.asarray(diff, dtype=np.float64)
+        diff = diff[np.isfinite(diff)]
+        rep[name] = {"max": float(np.abs(diff).max(initial=0.0)), "std": float(diff.std()) if diff.size else 0.0}
+
+    put("entropy", gpu["entropy"].astype(np.float64) - ref_unrounded["entropy"])
+    if has_target and "target_logp" in gpu:
+        put("target_logp", gpu["target_logp"].astype(np.float64) - ref_unrounded["target_logp"])
+    p_ref = ref_unrounded["topk_p"]
+    p_gpu = gpu["topk_p"].astype(np.float64)
+    ok = (p_ref > P_FLOOR) & (p_gpu > 0)
+    put("log_topk_p", np.log(p_gpu[ok]) - np.log(p_ref[ok]))
+    rep["topk_id_positions_differing"] = int((gpu["topk_ids"].astype(np.int64) != ref_unrounded["topk_ids"]).sum())
+    rep["topk_id_positions"] = int(p_ref.size)
+    return rep
 
 
 def check_invariants(gpu, V, k, has_target=True, label=""):

@@ -10,13 +10,11 @@ import oracle.lens_oracle as O
 from paper_2604_06483_amd import binding as LL
 from paper_2604_06483_amd import workloads as WL
 from tests import parity as P
+from tests.conftest import say
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
-
-def say(msg):
-    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
 
 
 @pytest.mark.parametrize("L,C,T,d,steps", [

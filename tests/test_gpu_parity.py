@@ -10,13 +10,11 @@ import oracle.lens_oracle as O
 from paper_2604_06483_amd import binding as LL
 from paper_2604_06483_amd import workloads as WL
 from tests import parity as P
+from tests.conftest import say
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
-
-def say(msg):
-    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
 
 
 @pytest.fixture(params=[2, 1], ids=["dma-panel", "fused-norm"], autouse=True)
@@ -214,7 +212,9 @@ def test_paper_output_format_bias_and_topk_softmax():
     want_p = O.topk_renormalised(ref["topk_p"])
     assert np.max(np.abs(got["topk_p"] - want_p)) <= P.TOL_P
     np.testing.assert_allclose(got["topk_p"].sum(1), 1.0, atol=1e-5)
-    assert np.array_equal(got["topk_ids"], ref["topk_ids"]) or np.mean(got["topk_ids"] != ref["topk_ids"]) < 0.01
+    P.validate_ids(got["topk_ids"], ref, "bias + top-k softmax")              # equal, or a near-tie of the oracle's logits
+    big = want_p > P.P_FLOOR
+    assert np.max(np.abs(np.log(got["topk_p"][big].astype(np.float64)) - np.log(want_p[big]))) <= P.TOL_LOG_P
     assert np.max(np.abs(got["entropy"] - ref["entropy"])) <= P.TOL_ENT      # still full-vocabulary
     assert np.max(np.abs(got["target_logp"] - ref["target_logp"])) <= P.TOL_LOGP
     # no bias, flag only, equals renormalising the plain result
@@ -264,23 +264,69 @@ def test_timed_variant_matches():
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("name", ["qwen3-4b", "llama31-8b", "qwen3-32b", "llama31-70b"])
 def test_full_size_config_sampled_rows(name, gemm_path):
-    if gemm_path != 2:
-        pytest.skip("full sizes run in the configuration the benchmark times (the default kernel)")
-    LL.ll_set_gemm_path(0)
+    # The default kernel (the configuration the benchmark times) runs all four; the register-staged kernel, with the
+    # norm applied inside the A-tile load, runs the first of them at full size on a smaller row sample.
+    if gemm_path != 2 and name != "qwen3-4b":
+        pytest.skip("the register-staged kernel runs one full-size config (qwen3-4b); the others are the default kernel's")
+    if gemm_path == 2:
+        LL.ll_set_gemm_path(0)
     cfg = WL.CONFIGS[name]
-    say(f"full size {name}: N={cfg.N} d={cfg.d} V={cfg.V} k={cfg.k}")
+    say(f"full size {name}: N={cfg.N} d={cfg.d} V={cfg.V} k={cfg.k}, kernel path {gemm_path}")
     w = WL.make_workload(cfg, DEV)
     got = run_project(w)
     P.check_invariants(got, cfg.V, cfg.k, label=name)
-    rows = WL.sample_rows(cfg, 256)
+    rows = WL.sample_rows(cfg, 256 if gemm_path == 2 else 64)
     ref = oracle_for(w, rows)
     rep = P.compare(P.take(got, rows), ref, cfg.k, label=name)
-    say(f"{name}: {rep}")
+    say(f"{name}: {P.R1_STATEMENT}")
+    say(f"{name}: against the gate oracle: {rep}")
+    if gemm_path == 2:
+        sub = rows[:: max(1, len(rows) // 64)]
+        hb = WL.bf16_bits(w.hidden.reshape(-1, cfg.d)[torch.as_tensor(sub, device=DEV)])
+        unr = P.oracle_rows(hb, WL.bf16_bits(w.gamma), WL.bf16_bits(w.W_U), cfg.eps, cfg.k,
+                            w.target_ids.cpu().numpy()[sub], round_a=False)
+        say(f"{name}: deviation from the un-rounded oracle on {len(sub)} rows (reported, not gated): "
+            f"{P.deviation_from_unrounded(P.take(got, sub), unr)}")
     # the Gaussian unembedding predicts the mean entropy: log V - var(z)/2 (a sanity band, not the gate)
     a = O.rmsnorm(WL.bf16_bits(w.hidden.reshape(-1, cfg.d)[torch.as_tensor(rows, device=DEV)]),
                   WL.bf16_bits(w.gamma), cfg.eps)
     pred = math.log(cfg.V) - 0.5 * 0.02 ** 2 * np.sum(a * a, axis=1)
     assert abs(float(np.mean(got["entropy"][rows])) - float(np.mean(pred))) < 0.05
+    del w
+    torch.cuda.empty_cache()
+
+
+def test_full_size_paper_output_format(gemm_path):
+    """ll_project_ex at the size the headline metric is quoted on: Eq. (1) with its bias b, probabilities over the
+    k = 3 selected logits only (Sec. 3.3, the format of the paper's heatmaps), sampled rows against the oracle."""
+    if gemm_path != 2:
+        pytest.skip("the default kernel is the one a bias selects; the other kernel's bias path is covered at small sizes")
+    LL.ll_set_gemm_path(0)
+    cfg = WL.CONFIGS["llama31-70b"]
+    k = 3
+    say(f"full size ll_project_ex llama31-70b: bias + top-k-only softmax, k={k}")
+    w = WL.make_workload(cfg, DEV)
+    g = torch.Generator(device=DEV).manual_seed(17)
+    bias = torch.randn((cfg.V,), generator=g, device=DEV) * 0.5
+    res = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, k, w.target_ids, bias=bias, topk_softmax=True)
+    torch.cuda.synchronize()
+    got = P.to_numpy(res)
+    rows = WL.sample_rows(cfg, 128)
+    hb = WL.bf16_bits(w.hidden.reshape(-1, cfg.d)[torch.as_tensor(rows, device=DEV)])
+    ref = P.oracle_rows(hb, WL.bf16_bits(w.gamma), WL.bf16_bits(w.W_U), cfg.eps, k, w.target_ids.cpu().numpy()[rows],
+                        bias=bias.cpu().numpy())
+    sub = P.take(got, rows)
+    P.validate_ids(sub["topk_ids"], ref, "70B ll_project_ex")
+    want_p = O.topk_renormalised(ref["topk_p"])
+    assert np.max(np.abs(sub["topk_p"] - want_p)) <= P.TOL_P
+    assert np.max(np.abs(np.log(sub["topk_p"].astype(np.float64)) - np.log(want_p))) <= P.TOL_LOG_P
+    np.testing.assert_allclose(got["topk_p"].sum(1), 1.0, atol=1e-5)            # every row: a distribution over the k
+    assert np.max(np.abs(sub["entropy"] - ref["entropy"])) <= P.TOL_ENT         # still full-vocabulary
+    assert np.max(np.abs(sub["target_logp"] - ref["target_logp"])) <= P.TOL_LOGP
+    # the bias matters at this size: without it the sampled rows' entropies differ by far more than the tolerance
+    plain = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, k, w.target_ids)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(plain[3].cpu().numpy()[rows] - ref["entropy"])) > 10 * P.TOL_ENT
     del w
     torch.cuda.empty_cache()
 

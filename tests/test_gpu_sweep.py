@@ -10,14 +10,12 @@ import oracle.lens_oracle as O
 from paper_2604_06483_amd import binding as LL
 from paper_2604_06483_amd import workloads as WL
 from tests import parity as P
+from tests.conftest import say
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 ALPHAS9 = [-4.0, -3.0, -2.0, -1.0, 0.0, 1.0, 2.0, 3.0, 4.0]
 
-
-def say(msg):
-    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
 
 
 def direction(d, seed=3):

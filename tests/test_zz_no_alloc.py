@@ -8,12 +8,11 @@ import torch
 from paper_2604_06483_amd import binding as LL
 from paper_2604_06483_amd import workloads as WL
 
+from tests.conftest import say
+
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
-
-def say(msg):
-    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
 
 
 def both(cfg, seed):
