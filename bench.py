@@ -4,10 +4,13 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config llama31-70b] [--no-cpu-baseline]
 
 A step is one pass of the whole path over one synthetic batch of the chosen config:
-ll_project on all N = L*T lens rows (RMS statistics, fused norm + unembedding GEMM + softmax /
+ll_project on all N = L*T lens rows (normalised panel, fused unembedding GEMM + softmax /
 top-k / target epilogue, split merge, in row passes of 8192), then the steering pair
 (ll_steer_vector on 64 + 64 label-position rows, ll_steer_inject on the middle layer's T rows).
-All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+All inputs are resident in HBM before the timed region.  The timed region calls the plain
+entry points; the per-kernel split behind `roofline` comes from the same number of steps run
+right afterwards through ll_project_timed (HIP events around every launch, on the launch
+stream).  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -48,10 +51,11 @@ def measured_traffic(config_name):
     return float(m_t.group(1))
 
 
-def cpu_baseline(w, gpu_np, R):
-    """The CPU oracle as it stands, timed on a stratified R-row sample of the same workload; also
-    compares the GPU's rows with it (reported, the tests are the gate)."""
-    import numpy as np
+def cpu_baseline(w, gpu_np, R, R_unrounded):
+    """The CPU oracle as it stands, timed on a stratified R-row sample of the same workload; also compares the
+    GPU's rows with it (reported, the tests are the gate) and reports the GPU's deviation from the oracle that
+    does not round the normalised row to bf16 (on R_unrounded of those rows).  The only place of this file that
+    loads the oracle."""
     import torch
     from threadpoolctl import threadpool_info
 
@@ -67,7 +71,13 @@ def cpu_baseline(w, gpu_np, R):
     ref = P.oracle_rows(hb, gb, wb, cfg.eps, cfg.k, tgt)
     dt = time.perf_counter() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    rep = P.compare(P.take(gpu_np, rows), ref, cfg.k, label="bench sample")
+    rep = {"gate": P.R1_STATEMENT}
+    rep.update(P.compare(P.take(gpu_np, rows), ref, cfg.k, label="bench sample"))
+    del ref
+    pick = slice(None, None, max(1, len(rows) // max(1, R_unrounded)))
+    unr = P.oracle_rows(hb[pick], gb, wb, cfg.eps, cfg.k, tgt[pick], round_a=False)
+    rep["deviation_from_unrounded_oracle"] = dict(P.deviation_from_unrounded(P.take(gpu_np, rows[pick]), unr),
+                                                  rows=int(len(rows[pick])))
     base = {
         "value": len(rows) / dt, "unit": "rows/s", "cores": int(threads), "kind": "oracle",
         "sample": f"{len(rows)} of {cfg.N} rows (stratified: every layer, both ends of every 8192-row pass), "
@@ -87,6 +97,7 @@ def main():
     ap.add_argument("--sample-rows", type=int, default=1024)   # ~12 s of host time on 16 cores
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-vendor-gemm", action="store_true", help="skip the vendor-library GEMM context figure")
+    ap.add_argument("--no-aux", action="store_true", help="skip the figures taken outside the timed steps")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -100,7 +111,6 @@ def main():
 
     from paper_2604_06483_amd import binding as LL
     from paper_2604_06483_amd import workloads as WL
-    from tests import parity as P
 
     dev = "cuda:0"
     cfg = WL.CONFIGS[args.config]
@@ -117,24 +127,25 @@ def main():
     steered = torch.empty_like(layer)
     stream = torch.cuda.current_stream()
 
-    phase = [0.0, 0.0, 0.0]
-    steer_ms = [0.0, 0.0]
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(max(K, 1))]
 
-    def step(record):
+    def step(i, timed_variant=False):
+        """One step; events of step i (None: not recorded) on the launch stream around the three calls."""
+        e = ev[i] if i is not None else None
+        if e:
+            e[0].record(stream)
         res = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, k, w.target_ids, workspace=ws, out=out,
-                            stream=stream, timed=True)
-        ev[0].record(stream)
+                            stream=stream, timed=timed_variant)
+        if e:
+            e[1].record(stream)
         LL.ll_steer_vector(base, target, True, workspace=sws, out=v, stream=stream)
-        ev[1].record(stream)
+        if e:
+            e[2].record(stream)
         LL.ll_steer_inject(layer, w.gamma, cfg.eps, v, 2.0, out=steered, stream=stream)
-        ev[2].record(stream)
-        if record:
-            ev[2].synchronize()
-            for i in range(3):
-                phase[i] += res[4][i]
-            steer_ms[0] += ev[0].elapsed_time(ev[1])
-            steer_ms[1] += ev[1].elapsed_time(ev[2])
+        if e:
+            e[3].record(stream)
+        return res
 
     if args.traffic_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
@@ -143,19 +154,35 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     for _ in range(args.warmup):
-        step(False)
+        step(None)
+    # ---- the timed region: exactly K steps through the plain entry points
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(True)
+    for i in range(K):
+        step(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    K = args.steps
     ms_per_step = dt / K * 1e3
+    project_ms = sum(e[0].elapsed_time(e[1]) for e in ev[:K]) / K
+    steer_ms = [sum(e[1].elapsed_time(e[2]) for e in ev[:K]) / K, sum(e[2].elapsed_time(e[3]) for e in ev[:K]) / K]
+
+    # ---- the same K steps again, straight afterwards, through ll_project_timed: HIP events around every kernel
+    # launch of the projection, recorded on the launch stream (the per-kernel split and the roofline figure)
+    phase = [0.0, 0.0, 0.0]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(K):
+        res = step(None, timed_variant=True)
+        for j in range(3):
+            phase[j] += res[4][j]
+    torch.cuda.synchronize()
+    ms_per_instrumented_step = (time.perf_counter() - t1) / K * 1e3
 
     passes = (N + cfg.chunk_rows - 1) // cfg.chunk_rows
     gemm_ms = phase[1] / K                      # all passes of one step
     tflops = cfg.flop / (gemm_ms * 1e-3) / 1e12
+    panel_kernel = "ll_norm_panel_kernel" if d % 64 == 0 else "ll_rms_stats_kernel"
+    panel_bytes = (4.0 if d % 64 == 0 else 2.0) * N * d           # the panel kernel reads and writes every row
     result = {
         "metric": "lens rows/sec (layer x token), fused norm+unembed+top-k",
         "value": N / (dt / K), "unit": "rows/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
@@ -166,24 +193,28 @@ def main():
                    "N": N, "d": d, "V": V, "k": k},
         "tflops_whole_step": cfg.flop / (dt / K) / 1e12,
         "frac_bf16_peak_whole_step": cfg.flop / (dt / K) / 1e12 / PEAK_BF16_TFLOPS,
+        "ll_project_ms": project_ms,            # HIP-event pair around the plain ll_project call, timed steps
         "roofline": {
             "kernel": "ll_lens_gemm_dma_kernel", "bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS, "traffic": measured_traffic(cfg.name),
             "launches_per_step": passes, "avg_launch_ms": gemm_ms / passes,
             "flop_per_row": 2.0 * d * V,
+            "measured_over": f"{K} instrumented steps (ll_project_timed) run directly after the {K} timed steps",
+            "ms_per_instrumented_step": ms_per_instrumented_step,
         },
-        "phases_ms_per_step": {"rms_stats": phase[0] / K, "lens_gemm": gemm_ms, "merge": phase[2] / K,
-                               "steer_vector": steer_ms[0] / K, "steer_inject": steer_ms[1] / K},
+        "phases_ms_per_step": {panel_kernel.replace("ll_", "").replace("_kernel", ""): phase[0] / K, "lens_gemm": gemm_ms,
+                               "merge": phase[2] / K, "steer_vector": steer_ms[0], "steer_inject": steer_ms[1]},
         "aux_hbm": {
-            "rms_stats_GBs": 2.0 * N * d / (phase[0] / K * 1e-3) / 1e9,
-            "steer_inject_GBs": 4.0 * cfg.T * d / (steer_ms[1] / K * 1e-3) / 1e9,
-            "steer_vector_GBs": 2.0 * 128 * d / (steer_ms[0] / K * 1e-3) / 1e9,
+            # bytes the kernel moves by its algorithm / its summed launch time inside the instrumented steps
+            panel_kernel.replace("ll_", "").replace("_kernel", "") + "_GBs": panel_bytes / (phase[0] / K * 1e-3) / 1e9,
+            "steer_inject_GBs": 4.0 * cfg.T * d / (steer_ms[1] * 1e-3) / 1e9,
+            "steer_vector_GBs": 2.0 * 128 * d / (steer_ms[0] * 1e-3) / 1e9,
             "peak_GBs": PEAK_HBM_GBS,
         },
         "paper_context": "paper reports end-to-end generation+capture+projection on 4x RTX A6000: 20-100 tok/s, "
                          "up to 41x vs its baseline, up to 7x less activation memory; no projection-only figure",
     }
-    # HBM-bound kernels at sizes where bandwidth (not launch latency) shows; outside the timed region.
+
     def timed_ms(fn, reps=3):
         fn()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -194,35 +225,92 @@ def main():
         b.synchronize()
         return a.elapsed_time(b) / reps
 
+    if not args.no_aux:
+        aux_figures(result, args, cfg, w, LL, torch, timed_ms, ws, sws, v, steered, layer, l_star, stream, tflops, project_ms)
+    if not args.no_cpu_baseline:
+        gpu_np = {"topk_ids": out[0].cpu().numpy(), "topk_p": out[1].cpu().numpy(), "target_logp": out[2].cpu().numpy(),
+                  "entropy": out[3].cpu().numpy()}
+        base_info, rep = cpu_baseline(w, gpu_np, args.sample_rows, max(1, args.sample_rows // 8))
+        result["cpu_baseline"] = base_info
+        result["parity_on_sample"] = rep
+    print(json.dumps(result))
+
+
+def aux_figures(result, args, cfg, w, LL, torch, timed_ms, ws, sws, v, steered, layer, l_star, stream, tflops, project_ms):
+    """Figures taken OUTSIDE the timed steps: the HBM-bound kernels at sizes where bandwidth (not launch latency)
+    shows, the paper-format call with a bias, the steering sweep, the three-activation-type capture store at the
+    paper's size, and the vendor library's plain GEMM as context."""
+    dev = w.hidden.device
+    N, d, V, k = cfg.N, cfg.d, cfg.V, cfg.k
     big = w.hidden.reshape(-1, d)
     nb = min(16384, N // 2)
     t_vec = timed_ms(lambda: LL.ll_steer_vector(big[:nb], big[nb:2 * nb], True, workspace=sws, out=v, stream=stream))
     all_out = torch.empty_like(big)
     t_inj = timed_ms(lambda: LL.ll_steer_inject(big, w.gamma, cfg.eps, v, 2.0, out=all_out, stream=stream))
+    t_raw = timed_ms(lambda: LL.ll_steer_inject_raw(big, v, 2.0, 1.0, 0.1, out=all_out, stream=stream))
     del all_out
-    # capture store: a prefill-sized append (every token of every layer at once) and one decoding step
-    store = torch.empty((cfg.L, 1, cfg.T, d), dtype=torch.bfloat16, device=dev)
-    t_app = timed_ms(lambda: LL.ll_capture_append(store, w.hidden, 0, stream=stream))
-    one = w.hidden[:, :1].contiguous()
-    t_dec = timed_ms(lambda: LL.ll_capture_append(store, one, cfg.T - 1, stream=stream), reps=20)
-    raw_out = torch.empty_like(big)
-    t_raw = timed_ms(lambda: LL.ll_steer_inject_raw(big, v, 2.0, 1.0, 0.1, out=raw_out, stream=stream))
-    del store, raw_out
-    # context for the figures above: what a plain device-to-device copy of 1 GiB reaches on this machine
+    # context for these figures: what a plain device-to-device copy of 1 GiB reaches on this box
     cp_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     cp_dst = torch.empty_like(cp_src)
     t_copy = timed_ms(lambda: cp_dst.copy_(cp_src), reps=5)
     del cp_src, cp_dst
-    result["aux_hbm"]["device_copy_1GiB_GBs"] = 2.0 * (1 << 30) / (t_copy * 1e-3) / 1e9
     result["aux_hbm"].update({
-        "capture_append_all_tokens_GBs": 4.0 * N * d / (t_app * 1e-3) / 1e9,
-        "capture_append_one_step_us": t_dec * 1e3, "capture_append_one_step_rows": cfg.L,
+        "device_copy_1GiB_GBs": 2.0 * (1 << 30) / (t_copy * 1e-3) / 1e9,
         "steer_inject_raw_all_rows_GBs": 4.0 * N * d / (t_raw * 1e-3) / 1e9,
         "steer_vector_large_GBs": 2.0 * 2 * nb * d / (t_vec * 1e-3) / 1e9, "steer_vector_large_rows": 2 * nb,
         "steer_inject_all_rows_GBs": 4.0 * N * d / (t_inj * 1e-3) / 1e9,
     })
-    # Dose-response sweep (outside the timed region): the middle layer's rows read out for nine alphas, once as
-    # one ll_steer_sweep pass over W_U and once as nine ll_steer_inject + ll_project(gamma=None, k=1) pairs.
+
+    # Eq. 1 with its bias b (paper-format output, k = 3 and probabilities over the k selected logits) against the plain call
+    g = torch.Generator(device=dev).manual_seed(17)
+    bias = torch.randn((V,), generator=g, device=dev) * 0.5
+    t_plain = timed_ms(lambda: LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, k, w.target_ids, workspace=ws, stream=stream),
+                       reps=2)
+    t_bias = timed_ms(lambda: LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, k, w.target_ids, workspace=ws, stream=stream,
+                                            bias=bias), reps=2)
+    t_paper = timed_ms(lambda: LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, 3, w.target_ids, workspace=ws, stream=stream,
+                                             bias=bias, topk_softmax=True), reps=2)
+    result["paper_format_output"] = {"ll_project_ms": t_plain, "ll_project_ex_bias_same_k_ms": t_bias,
+                                     "bias_over_plain": t_bias / t_plain, "ll_project_ex_bias_k3_topk_softmax_ms": t_paper}
+    del bias
+
+    # Capture store with three activation types per layer (attention, MLP and block output: paper Sec. 3.1 / the
+    # memory example of Sec. 3.2, 5.9 GB for 80 layers): filled by a prefill-sized append and single-token decoding
+    # steps, then projected as it stands (3 N lens rows).
+    C = 3
+    try:
+        store = torch.empty((cfg.L, C, cfg.T, d), dtype=torch.bfloat16, device=dev)
+        n_pre = cfg.T - 8
+        pre = w.hidden[:, None, :n_pre].expand(cfg.L, C, n_pre, d).reshape(cfg.L * C, n_pre, d).contiguous()
+        t_app = timed_ms(lambda: LL.ll_capture_append(store, pre, 0, stream=stream))
+        del pre
+        one = [w.hidden[:, None, t:t + 1].expand(cfg.L, C, 1, d).reshape(cfg.L * C, 1, d).contiguous()
+               for t in range(n_pre, cfg.T)]
+
+        def decode_steps():
+            for j, s in enumerate(one):
+                LL.ll_capture_append(store, s, n_pre + j, stream=stream)
+        t_dec = timed_ms(decode_steps, reps=5) / len(one)
+        tgt3 = w.target_ids.reshape(cfg.L, 1, cfg.T).expand(cfg.L, C, cfg.T).reshape(-1).contiguous()
+        n3 = cfg.L * C * cfg.T
+        ws3 = torch.empty(LL.ll_workspace_bytes(n3, d, V, k), dtype=torch.uint8, device=dev)
+        out3 = (torch.empty((n3, k), dtype=torch.int32, device=dev), torch.empty((n3, k), dtype=torch.float32, device=dev),
+                torch.empty((n3,), dtype=torch.float32, device=dev), torch.empty((n3,), dtype=torch.float32, device=dev))
+        t_p3 = timed_ms(lambda: LL.ll_project(store, w.gamma, w.W_U, cfg.eps, k, tgt3, workspace=ws3, out=out3, stream=stream),
+                        reps=1)
+        result["capture_three_types"] = {
+            "layers": cfg.L, "types": C, "tokens": cfg.T, "rows": n3, "store_GB": n3 * d * 2 / 1e9,
+            "append_prefill_tokens": n_pre, "append_prefill_GBs": 4.0 * cfg.L * C * n_pre * d / (t_app * 1e-3) / 1e9,
+            "append_decode_step_us": t_dec * 1e3, "append_decode_step_rows": cfg.L * C,
+            "project_ms": t_p3, "project_rows_per_s": n3 / (t_p3 * 1e-3),
+            "project_tflops": 2.0 * n3 * d * V / (t_p3 * 1e-3) / 1e12,
+        }
+        del store, one, tgt3, ws3, out3
+    except torch.OutOfMemoryError:                      # a smaller card: the figure is skipped, nothing else depends on it
+        result["capture_three_types"] = None
+
+    # Dose-response sweep: the middle layer's rows read out for nine alphas, once as one ll_steer_sweep pass over W_U
+    # and once as nine ll_steer_inject + ll_project(gamma=None, k=1) pairs.
     if d % 64 == 0:
         alphas = [float(a) for a in range(-4, 5)]
         tgt_layer = w.target_ids.reshape(cfg.L, cfg.T)[l_star].contiguous()
@@ -238,10 +326,10 @@ def main():
         result["steer_sweep"] = {"rows": cfg.T, "n_alpha": len(alphas), "sweep_ms": t_sweep, "inject_project_pairs_ms": t_pairs,
                                  "speedup": t_pairs / t_sweep}
         del sww
-    # Context, outside the timed region: the vendor library's plain bf16 GEMM (torch.matmul, i.e. hipBLASLt) on
-    # one row pass of the same shape and the same operand values, with the logits written to HBM and none of the
-    # norm / softmax / top-k work.  Not the product path and not a target: it shows what this box's power and
-    # clocks give a dense bf16 contraction of this shape today.
+    # Context: the vendor library's plain bf16 GEMM (torch.matmul, i.e. hipBLASLt) on one row pass of the same shape
+    # and the same operand values, with the logits written to HBM and none of the norm / softmax / top-k work.  Not
+    # the product path and not a target: it shows what this box's power and clocks give a dense bf16 contraction of
+    # this shape today.
     if not args.no_vendor_gemm:
         rows = min(cfg.chunk_rows, N)
         a_rows = torch.empty((rows, d), dtype=torch.bfloat16, device=dev)
@@ -255,12 +343,6 @@ def main():
             "ms": t_blas, "tflops": tf_blas, "frac_bf16_peak": tf_blas / PEAK_BF16_TFLOPS,
             "this_kernel_over_vendor": tflops / tf_blas,
         }
-    if not args.no_cpu_baseline:
-        gpu_np = P.to_numpy(out)
-        base_info, rep = cpu_baseline(w, gpu_np, args.sample_rows)
-        result["cpu_baseline"] = base_info
-        result["parity_on_sample"] = rep
-    print(json.dumps(result))
 
 
 if __name__ == "__main__":

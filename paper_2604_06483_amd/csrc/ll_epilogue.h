@@ -62,6 +62,8 @@ struct GemmArgs {
   float4* sweep_stats;      // [rows, splits, n_alpha]  (m, S, T, bits of the arg max id)
   float* sweep_ztgt;        // [rows, splits]           logit of the target id at alpha = 0
   int au_stride, n_alpha;
+  // sharing top-k thresholds between the vocabulary splits of a row (nullptr: off)
+  unsigned* bound;          // [rows] lower bounds on each row's k-th best logit, as ordered keys; zero at launch
 };
 
 // ---------------------------------------------------------------------------------------
@@ -72,6 +74,17 @@ struct GemmArgs {
 // logits ascending id.  A workgroup meets its vocabulary ids in increasing order, so a new
 // candidate never outranks an equal logit already listed and a strict comparison is exact.
 // ---------------------------------------------------------------------------------------
+// Floats as unsigned keys of the same order, so that an integer atomic max is a float max.  Key 0
+// is below every float's key: "nothing known yet".
+__device__ __forceinline__ unsigned float_key(float f) {
+  const unsigned b = __float_as_uint(f);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key_float(unsigned k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+constexpr unsigned KEY_NEG_INF = 0x007fffffu;   // float_key(-inf)
+
 template <int KR>
 struct RowState {
   float m = -INFINITY;
@@ -79,6 +92,7 @@ struct RowState {
   float t = 0.f;
   float z_tgt = -INFINITY;  // logit of the target id, once its tile has passed
   int tgt = -1;             // target id of the row (-1: none)
+  float shared_bound = -INFINITY;   // nothing at or below this can reach the row's final top k (see exchange_bound)
   float lv[KR];             // top logits
   int li[KR];               // their ids
   __device__ __forceinline__ void init() {
@@ -89,6 +103,8 @@ struct RowState {
     }
   }
   __device__ __forceinline__ float tau() const { return lv[KR - 1]; }
+  // A candidate has to beat both the row's own KR-th best and what the other splits report.
+  __device__ __forceinline__ float threshold() const { return fmaxf(lv[KR - 1], shared_bound); }
   // Branch-free sorted insert: slot j takes its upper neighbour if the candidate goes above that
   // neighbour, the candidate if it goes exactly here, and keeps its entry otherwise.  For the
   // logits that is the median of (upper neighbour, own entry, candidate): one instruction.  Four
@@ -266,8 +282,8 @@ __device__ __forceinline__ void epilogue_group(const ACC& acc, RowState<KR>& st,
   // (a divergent branch: the other lanes are masked off and cost no energy, which is what counts
   // on a power-limited chip): mark the candidates against that threshold, then insert them in
   // id order.
-  if (gmax > st.tau()) {
-    const float tau0 = st.tau();
+  if (gmax > st.threshold()) {
+    const float tau0 = st.threshold();
     // bit o of mask: x[o] > tau0.  Two instructions per entry: the comparison, then the mask
     // doubled plus the comparison's result as carry-in (entries taken from 31 down to 0).  Four
     // entries at a time, comparisons first: a VALU result in an SGPR must not be read by the
@@ -313,6 +329,40 @@ __device__ __forceinline__ void epilogue_tile(const ACC& acc, RowState<KR>& st, 
   epilogue_group<7, KR, BIAS, ACC>(acc, st, v0, V, partial, bias);
 }
 
+// The workgroups that sweep other parts of the vocabulary for the same rows tell each other how
+// good a logit has to be.  A split's k-th best logit so far is a lower bound on the row's k-th best
+// overall, and nothing below the largest such bound can be in the final top k; without it every
+// split collects candidates against its own slowly rising threshold (k (1 + ln(n/k)) insertions per
+// row for n vocabulary entries: eight short streams cost far more than one long one).  After each
+// tile a lane picks up the row's shared bound and publishes its own (atomic max on the key).  A
+// logit EQUAL to the bound may still belong in the top k (a smaller id wins a tie), so the
+// threshold is the next float below it.  The final result does not depend on timing: a bound only
+// removes entries that cannot be in the final top k; a split's own list may end up with fewer
+// than k real entries, which the merge treats as absent.
+// Placed at the END of the tile's epilogue: the operand loads in flight were sent before the
+// epilogue began and have landed, so the wait for this one load costs one trip to the L2 and no
+// more.  The publish needs no answer and is never waited for.
+template <int KR>
+__device__ __forceinline__ void exchange_bound(RowState<KR>& st, const GemmArgs& p, int my_row) {
+  if (p.bound == nullptr) return;
+  unsigned* const b = p.bound + min(my_row, p.rows - 1);
+  asm volatile("" ::: "memory");
+  const unsigned fresh = __hip_atomic_load(b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  st.shared_bound = fresh > KEY_NEG_INF ? key_float(fresh - 1u) : -INFINITY;
+  // own bound: the k-th best of this split's list (k <= KR, KR - k < 12)
+  // (each entry goes through an empty asm statement: a plain chain of selects on k the optimiser
+  // folds into an indexed access and moves the whole list to scratch memory)
+  float mine = st.lv[KR - 1];
+#pragma unroll
+  for (int j = KR - 2; j >= 0 && j >= KR - 12; --j) {
+    float entry = st.lv[j];
+    asm volatile("" : "+v"(entry));
+    mine = (p.k - 1 == j) ? entry : mine;
+  }
+  if (my_row < p.rows && mine > st.shared_bound) __hip_atomic_fetch_max(b, float_key(mine), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  asm volatile("" ::: "memory");
+}
+
 // Per-(row, split) partial results: (m, S, T, z_target) and the k best (logit bits, id) pairs.
 template <int KR>
 __device__ __forceinline__ void epilogue_store(const GemmArgs& p, const RowState<KR>& st, int my_row, int split) {
@@ -334,8 +384,10 @@ struct TopKEpilogue {   // a5..a7: softmax statistics, k best logits, target log
     st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
   }
   template <class ACC>
-  static __device__ __forceinline__ void tile(const ACC& acc, State& st, int v0, const GemmArgs& p) {
+  static __device__ __forceinline__ void tile(const ACC& acc, State& st, int v0, const GemmArgs& p, int my_row) {
     epilogue_tile<KR, BIAS, ACC>(acc, st, v0, p.V, p.bias);
+    // (the longest list together with a bias leaves no register for the exchange: that one kernel goes without)
+    if (!(KR == 32 && BIAS)) exchange_bound(st, p, my_row);
   }
   static __device__ __forceinline__ void store(const GemmArgs& p, const State& st, int my_row, int split) {
     epilogue_store(p, st, my_row, split);
@@ -430,7 +482,7 @@ struct SweepEpilogue {
     st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
   }
   template <class ACC>
-  static __device__ __forceinline__ void tile(const ACC& acc, State& st, int v0, const GemmArgs& p) {
+  static __device__ __forceinline__ void tile(const ACC& acc, State& st, int v0, const GemmArgs& p, int /*my_row*/) {
     const bool partial = v0 + BM > p.V;
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");   // as in epilogue_tile: let the last MFMA drain
     sweep_group<0, ACC>(acc, st, v0, p.V, partial, p);

@@ -357,7 +357,7 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
       LL_STAGE(LL_MFMA16)
     }
 #undef LL_STAGE
-    EPI::tile(acc, st, tile * BM, p);
+    EPI::tile(acc, st, tile * BM, p, my_row);
   }
 #undef LL_PAIR
 #undef LL_T

@@ -101,6 +101,10 @@ __global__ __launch_bounds__(256) void ll_pad_bias_kernel(const float* __restric
     padded[i] = i < V ? bias[i] : 0.f;
 }
 
+__global__ __launch_bounds__(256) void ll_zero_u32_kernel(unsigned* __restrict__ p, int n) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0u;
+}
+
 __global__ __launch_bounds__(256) void ll_fill_f32_kernel(float* __restrict__ p, int n, float value) {
   for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = value;
 }
@@ -191,15 +195,28 @@ __device__ __forceinline__ int group_min_int(int x, int width) {
   return x;
 }
 
-// One wavefront per row, lane s = split s (splits <= 64).
+// One wavefront per row, lane s = split s (splits <= 64).  The row's lists (splits x k pairs, contiguous in the
+// workspace) are first copied into LDS with coalesced loads: the k steps of the merge are a chain, each needing the
+// next entry of whichever list won the step before, and from LDS that costs a fraction of a trip to memory.
+// Dynamic LDS: 4 wavefronts x splits x k x 8 bytes (at most 64 KB).
 __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict__ stats, const uint2* __restrict__ top,
                                                        int rows, int splits, int k, int V, int topk_softmax,
                                                        const int32_t* __restrict__ target, int32_t* __restrict__ out_ids,
                                                        float* __restrict__ out_p, float* __restrict__ out_logp,
-                                                       float* __restrict__ out_entropy) {
-  const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (row >= rows) return;
+                                                       float* __restrict__ out_entropy, unsigned* __restrict__ bound) {
+  extern __shared__ __align__(8) uint2 lists[];
+  const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * (blockDim.x >> 6) + wave;
+  const bool valid = row < rows;          // (no early return: every wavefront reaches the barrier)
+  const int n_entries = splits * k;
+  uint2* mine = lists + wave * n_entries;
+  if (valid) {
+    const uint2* src = top + (int64_t)row * n_entries;
+    for (int i = lane; i < n_entries; i += 64) mine[i] = src[i];
+  }
+  __syncthreads();
+  if (!valid) return;
   const bool live = lane < splits;
   float4 q = make_float4(-INFINITY, 0.f, 0.f, -INFINITY);
   if (live) q = stats[(int64_t)row * splits + lane];
@@ -210,6 +227,7 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict_
   const float zt = wave_max(q.w);
   const float logS = logf(S);
   if (lane == 0) {
+    if (bound != nullptr) bound[row] = 0u;   // the projection kernel of this pass is done with it: clear it for the next pass
     out_entropy[row] = (M - T / S) + logS;
     if (target != nullptr) {
       const int t = target[row];
@@ -218,7 +236,7 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict_
   }
   // k-way merge of the per-split sorted lists (descending logit, ascending id): every lane holds the
   // head of its list; the wavefront's best head goes out and that lane moves on.
-  const uint2* tl = top + ((int64_t)row * splits + lane) * k;
+  const uint2* tl = mine + (live ? lane : 0) * k;
   int head = 0;
   float z = -INFINITY;
   int id = INT_MAX;
@@ -228,7 +246,8 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict_
     id = (int)e.y;
   }
   float z0 = 0.f, sk = 0.f;   // top-k-only softmax: the largest selected logit and the sum over the selection
-  float mine = 0.f;           // lane j keeps the j-th selected logit
+  float my_z = 0.f;           // lane j keeps the j-th selected logit and id, written out together at the end
+  int my_id = 0;
   int width = 1;   // lanes that hold a list, rounded up to a power of two (lanes past `splits` hold the neutral head)
   while (width < splits) width <<= 1;
   for (int j = 0; j < k; ++j) {
@@ -247,16 +266,20 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict_
     }
     // (lanes past `width` did not take part: what they keep comes from lane 0)
     const float out_z = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(bz)));
+    const int out_id = __builtin_amdgcn_readfirstlane(bi);
     if (j == 0) z0 = out_z;
     sk += __builtin_amdgcn_exp2f((out_z - z0) * LOG2E);
-    if (lane == j) mine = out_z;
-    if (lane == 0) {
-      out_ids[(int64_t)row * k + j] = bi;
-      if (!topk_softmax) out_p[(int64_t)row * k + j] = __builtin_amdgcn_exp2f(((out_z - M) - logS) * LOG2E);
+    if (lane == j) {
+      my_z = out_z;
+      my_id = out_id;
     }
   }
-  // The paper's own probabilities (Sec. 3.3): a softmax over the k selected logits only.
-  if (topk_softmax && lane < k) out_p[(int64_t)row * k + lane] = __builtin_amdgcn_exp2f((mine - z0) * LOG2E) * (1.0f / sk);
+  if (lane < k) {
+    out_ids[(int64_t)row * k + lane] = my_id;
+    // full-vocabulary probability, or the paper's own (Sec. 3.3): a softmax over the k selected logits only
+    out_p[(int64_t)row * k + lane] = topk_softmax ? __builtin_amdgcn_exp2f((my_z - z0) * LOG2E) * (1.0f / sk)
+                                                  : __builtin_amdgcn_exp2f(((my_z - M) - logS) * LOG2E);
+  }
 }
 
 __global__ __launch_bounds__(256) void ll_sweep_merge_kernel(const float4* __restrict__ stats, const float* __restrict__ ztgt,
@@ -301,7 +324,7 @@ __global__ __launch_bounds__(256) void ll_sweep_merge_kernel(const float4* __res
 // host side
 // ---------------------------------------------------------------------------------------
 struct Plan {
-  size_t off_inv_rms, off_bias, off_stats, off_top, off_panel, total;
+  size_t off_inv_rms, off_bound, off_bias, off_stats, off_top, off_panel, total;
   int64_t lda;
 };
 
@@ -319,6 +342,8 @@ Plan make_plan(const ll_shape* s, int k, int chunk_rows = CHUNK_ROWS) {
   size_t off = 0;
   p.off_inv_rms = off;
   off = align_up(off + (size_t)s->N * sizeof(float), 256);
+  p.off_bound = off;  // per-row top-k bounds shared between the splits of a pass
+  off = align_up(off + (size_t)(s->N < chunk_rows ? s->N : chunk_rows) * sizeof(unsigned), 256);
   p.off_bias = off;   // the bias padded to whole tiles (ll_project_ex)
   off = align_up(off + (size_t)((s->V + BM - 1) / BM) * BM * sizeof(float), 256);
   const size_t rows = (size_t)(s->N < chunk_rows ? s->N : chunk_rows);
@@ -408,19 +433,21 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
 
   // Timing (ll_project_timed only): events are recorded in-stream around every kernel and read
   // after one synchronisation at the end, so the kernels run back to back as in ll_project.
-  std::vector<hipEvent_t> ev;
+  // (the events are created once per thread and kept: a timed call costs no event creation after the first)
+  static thread_local std::vector<hipEvent_t> ev_pool;
+  size_t n_ev = 0;
   auto mark = [&]() -> hipError_t {
     if (!phase_ms) return hipSuccess;
-    hipEvent_t e = nullptr;
-    hipError_t rc = hipEventCreate(&e);
-    if (rc != hipSuccess) return rc;
-    ev.push_back(e);
-    return hipEventRecord(e, stream);
+    if (n_ev == ev_pool.size()) {
+      hipEvent_t e = nullptr;
+      hipError_t rc = hipEventCreate(&e);
+      if (rc != hipSuccess) return rc;
+      ev_pool.push_back(e);
+    }
+    return hipEventRecord(ev_pool[n_ev++], stream);
   };
-  auto finish = [&](int rc) {
-    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
-    return rc;
-  };
+  auto finish = [&](int rc) { return rc; };
+  const std::vector<hipEvent_t>& ev = ev_pool;
 #define LL_CHECK_F(expr)                                   \
   do {                                                     \
     hipError_t e__ = (expr);                               \
@@ -428,6 +455,15 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   } while (0)
 
   const int tiles = (V + BM - 1) / BM;
+  // Top-k bounds shared between the vocabulary splits of a row (direct-to-LDS kernel): zero at the start of a
+  // pass; the merge kernel of a pass clears them again for the next one.
+  unsigned* bound = nullptr;
+  if (dma) {
+    bound = reinterpret_cast<unsigned*>(ws + plan.off_bound);
+    const int n_zero = (int)(N < chunk_rows ? N : chunk_rows);
+    hipLaunchKernelGGL(ll_zero_u32_kernel, dim3((n_zero + 255) / 256), dim3(256), 0, stream, bound, n_zero);
+    LL_CHECK_F(hipGetLastError());
+  }
   float* bias_padded = nullptr;
   if (bias != nullptr) {
     bias_padded = reinterpret_cast<float*>(ws + plan.off_bias);
@@ -476,22 +512,24 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     a.splits = splits;
     a.tiles = tiles;
     a.row_blocks = row_blocks;
+    a.bound = bound;
     const int grid = (row_blocks * splits + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
     LL_CHECK_F(mark());
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHREADS), lds, stream, a);
     LL_CHECK_F(hipGetLastError());
     LL_CHECK_F(mark());
-    hipLaunchKernelGGL(ll_merge_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, (const float4*)stats, (const uint2*)top,
+    hipLaunchKernelGGL(ll_merge_kernel, dim3((rows + 3) / 4), dim3(256), (size_t)4 * splits * k * sizeof(uint2), stream,
+                       (const float4*)stats, (const uint2*)top,
                        rows, splits, k, V, (flags & LL_FLAG_TOPK_SOFTMAX) ? 1 : 0, a.target, out_topk_ids + r0 * k,
                        out_topk_p + r0 * k,
-                       out_target_logp ? out_target_logp + r0 : nullptr, out_entropy + r0);
+                       out_target_logp ? out_target_logp + r0 : nullptr, out_entropy + r0, bound);
     LL_CHECK_F(hipGetLastError());
     LL_CHECK_F(mark());
   }
   if (phase_ms) {
     LL_CHECK_F(hipStreamSynchronize(stream));
     phase_ms[0] = phase_ms[1] = phase_ms[2] = 0.f;
-    for (size_t i = 0; i + 3 < ev.size(); i += 4) {
+    for (size_t i = 0; i + 3 < n_ev; i += 4) {
       float ms = 0.f;
       LL_CHECK_F(hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
       phase_ms[0] += ms;

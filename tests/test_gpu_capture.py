@@ -71,6 +71,39 @@ def test_captured_store_is_what_the_projection_reads():
     P.compare(P.take(P.to_numpy(got), rows), want, k, label="captured store")
 
 
+def test_three_activation_types_at_the_papers_size():
+    """The capture store of the paper's memory example (Sec. 3.2: T = 1500, d = 8192, 80 layers, attention + MLP +
+    block outputs, about 5.9 GB) with the embedding output on top: 81 x 3 trajectories = 364 500 lens rows.  Filled
+    the way generation fills it (a prefill-sized append, then single-token decoding steps, then a multi-token
+    chunk), it must equal the concatenated slices bit for bit, and the projection reads it as it stands: sampled
+    rows against the oracle, every row against the invariants."""
+    base = WL.CONFIGS["llama31-70b"]
+    L, C, T, d, V, k = base.L, 3, base.T, base.d, base.V, base.k
+    say(f"capture -> project at full size: L={L} C={C} T={T} d={d} ({L * C * T} rows, {L * C * T * d * 2 / 1e9:.2f} GB)")
+    cfg = WL.LensConfig("capture-3types", L=L * C, T=T, d=d, V=V, k=k, n_outliers=4, outlier_scale=20.0)
+    w = WL.make_workload(cfg, DEV)                                # trajectory (l, c) = "layer" l * C + c of this workload
+    store = torch.full((L, C, T, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    t = 0
+    for n in (1200,) + (1,) * 40 + (260,):                        # prefill, 40 decoding steps, a trailing chunk
+        LL.ll_capture_append(store, w.hidden[:, t:t + n].contiguous(), t)
+        t += n
+    assert t == T
+    torch.cuda.synchronize()
+    assert torch.equal(store.reshape(L * C, T, d).view(torch.int16), w.hidden.view(torch.int16))     # a copy: bit for bit
+    del w.hidden
+    res = LL.ll_project(store, w.gamma, w.W_U, cfg.eps, k, w.target_ids)
+    torch.cuda.synchronize()
+    got = P.to_numpy(res)
+    P.check_invariants(got, V, k, label="capture-3types")
+    rows = WL.sample_rows(cfg, 96)
+    hb = WL.bf16_bits(store.reshape(-1, d)[torch.as_tensor(rows, device=DEV)])
+    ref = P.oracle_rows(hb, WL.bf16_bits(w.gamma), WL.bf16_bits(w.W_U), cfg.eps, k, w.target_ids.cpu().numpy()[rows])
+    rep = P.compare(P.take(got, rows), ref, k, label="capture-3types")
+    say(f"capture-3types: {rep}")
+    del store, w
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("N,d", [(300, 4096), (7, 328), (130, 8192), (33, 64), (20, 9000)])
 def test_steer_inject_raw(N, d):
     say(f"steer_inject_raw N={N} d={d}")
