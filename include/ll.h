@@ -171,8 +171,9 @@ int ll_steer_inject(const ll_shape* shape, const void* hidden, const void* gamma
 
 /*
  * Steering inside the model (paper Sec. 3.4, the unnumbered equation h' = h + alpha v after
- * Eq. 2, with the "magnitude clipping and layer-specific scaling" of its stability paragraph):
- * the raw activation of a wrapped layer is shifted along v, without any normalisation,
+ * Eq. 2, with the two safeguards of that section's stability paragraph: a per-layer scale and a
+ * bound on the size of the shift): the raw activation of a wrapped layer is shifted along v,
+ * without any normalisation,
  *
  *   s        = alpha * layer_scale
  *   beta[r]  = sign(s) * min(|s|, clip_ratio * ||hidden[r, :]||_2)     (clip_ratio > 0)
@@ -230,17 +231,33 @@ int ll_capture_append(const ll_capture_shape* shape, void* store, const void* sl
  *   out_top1_p   [n_alpha, N] fp32    its full-softmax probability
  *   out_target_logp [n_alpha, N] fp32 NaN where the target id is outside [0, V)
  *   out_entropy  [n_alpha, N] fp32    nats
- * Requirements beyond ll_project's: d a multiple of 64 (LL_EINVAL otherwise).  Workspace:
- * ll_steer_sweep_workspace_bytes(shape, n_alpha).  Same error, ownership, stream and N == 0
- * conventions as ll_project.
+ * Requirements beyond ll_project's: d at most 40960 (the direction v is held in LDS while
+ * u = W_U v is formed; LL_EINVAL beyond).  d a multiple of 64 runs on the direct-to-LDS kernel, any
+ * other multiple of 8 on the register-staged one.  Workspace: ll_steer_sweep_workspace_bytes(shape,
+ * n_alpha).  Same error, ownership, stream and N == 0 conventions as ll_project.
+ *
+ * ll_steer_sweep_topk: the same with the k most likely tokens per alpha and row instead of one
+ * (1 <= k <= LL_SWEEP_KMAX; the paper's figures list k = 3), sorted as in ll_project:
+ *   out_topk_ids [n_alpha, N, k] int32,  out_topk_p [n_alpha, N, k] fp32 (full-softmax probabilities)
+ * With k == 1 it is ll_steer_sweep.  With k > 1 the lists of four alphas are what fits the
+ * register file beside the accumulators, so the call makes ceil(n_alpha / 4) passes over W_U
+ * (nine alphas: three passes, against nine for ll_steer_inject + ll_project pairs).  Workspace:
+ * ll_steer_sweep_topk_workspace_bytes(shape, n_alpha, k).
  */
 #define LL_SWEEP_MAX 9
+#define LL_SWEEP_KMAX 4   /* longest top-k list of ll_steer_sweep_topk */
 size_t ll_steer_sweep_workspace_bytes(const ll_shape* shape, int n_alpha);
 int ll_steer_sweep(const ll_shape* shape, void* workspace, size_t workspace_bytes,
                    const void* hidden, const void* gamma, const void* W_U, float eps,
                    const float* v, const float* alphas, int n_alpha, const int32_t* target_ids,
                    int32_t* out_top1_ids, float* out_top1_p, float* out_target_logp, float* out_entropy,
                    void* stream);
+size_t ll_steer_sweep_topk_workspace_bytes(const ll_shape* shape, int n_alpha, int k);
+int ll_steer_sweep_topk(const ll_shape* shape, void* workspace, size_t workspace_bytes,
+                        const void* hidden, const void* gamma, const void* W_U, float eps,
+                        const float* v, const float* alphas, int n_alpha, int k, const int32_t* target_ids,
+                        int32_t* out_topk_ids, float* out_topk_p, float* out_target_logp, float* out_entropy,
+                        void* stream);
 
 /*
  * Chooses the projection kernel for ll_project calls of this process that start afterwards

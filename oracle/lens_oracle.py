@@ -210,27 +210,33 @@ def steer_inject(hidden_bits, gamma_bits, eps: float, v, alpha: float) -> np.nda
     return f64_to_bf16_bits(out)
 
 
-def steer_sweep(hidden_bits, gamma_bits, w_bits, eps: float, v, alphas, target_ids=None, round_a: bool = True) -> dict:
+def steer_sweep(hidden_bits, gamma_bits, w_bits, eps: float, v, alphas, target_ids=None, round_a: bool = True,
+                k: int = 1) -> dict:
     """Lens read-out of Eq. (3) for several steering strengths (Sec. 3.4, dose-response of Sec. 5).
 
     For every alpha: z_alpha = W_U (a + alpha v) with a the normalised row (rounded to bf16
     once, as in lens_project, when round_a), written out as the definition says: the steered
     rows are formed first, in fp64 and without any further rounding, then multiplied by W_U.
     Returns, per alpha and row, the arg max (smallest id on ties), its full-softmax
-    probability, the target log-probability and the entropy: arrays of shape [n_alpha, R].
+    probability, the target log-probability and the entropy: arrays of shape [n_alpha, R];
+    and the k most likely tokens with their probabilities and logits (the paper's figures
+    list k = 3 per cell), sorted as in softmax_summaries: arrays of shape [n_alpha, R, k].
     """
     a = rmsnorm(hidden_bits, gamma_bits, eps, round_a=round_a) if gamma_bits is not None else bf16_bits_to_f64(hidden_bits)
     vv = np.asarray(v, dtype=np.float64)
-    out = {"top1_ids": [], "top1_p": [], "target_logp": [], "entropy": []}
+    out = {"top1_ids": [], "top1_p": [], "target_logp": [], "entropy": [], "topk_ids": [], "topk_p": [], "topk_logits": []}
     for alpha in alphas:
         z = full_logits(a + float(alpha) * vv[None, :], w_bits)
-        sm = softmax_summaries(z, 1, target_ids)
+        sm = softmax_summaries(z, k, target_ids)
         out["top1_ids"].append(sm["topk_ids"][:, 0])
         out["top1_p"].append(sm["topk_p"][:, 0])
+        out["topk_ids"].append(sm["topk_ids"])
+        out["topk_p"].append(sm["topk_p"])
+        out["topk_logits"].append(sm["topk_logits"])
         if target_ids is not None:
             out["target_logp"].append(sm["target_logp"])
         out["entropy"].append(sm["entropy"])
-    return {k: np.stack(x) for k, x in out.items() if x}
+    return {name: np.stack(x) for name, x in out.items() if x}
 
 
 def steer_inject_raw(hidden_bits, v, alpha: float, layer_scale: float = 1.0, clip_ratio: float = 0.0) -> np.ndarray:

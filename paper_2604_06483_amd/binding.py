@@ -75,6 +75,12 @@ def lib() -> ctypes.CDLL:
                                      c_void_p, POINTER(c_float), c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                      c_void_p]
         L.ll_steer_sweep.restype = c_int
+        L.ll_steer_sweep_topk_workspace_bytes.argtypes = [POINTER(ll_shape), c_int, c_int]
+        L.ll_steer_sweep_topk_workspace_bytes.restype = c_size_t
+        L.ll_steer_sweep_topk.argtypes = [POINTER(ll_shape), c_void_p, c_size_t, c_void_p, c_void_p, c_void_p, c_float,
+                                          c_void_p, POINTER(c_float), c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p,
+                                          c_void_p, c_void_p]
+        L.ll_steer_sweep_topk.restype = c_int
         L.ll_steer_inject_raw.argtypes = [POINTER(ll_shape), c_void_p, c_void_p, c_float, c_float, c_float, c_void_p, c_void_p]
         L.ll_steer_inject_raw.restype = c_int
         L.ll_capture_append.argtypes = [POINTER(ll_capture_shape), c_void_p, c_void_p, c_int64, c_int64, c_void_p]
@@ -248,17 +254,21 @@ def ll_steer_inject(hidden, gamma, eps, v, alpha, *, stream=None, out=None):
 
 
 LL_SWEEP_MAX = 9
+LL_SWEEP_KMAX = 4
 
 
-def ll_steer_sweep_workspace_bytes(N: int, d: int, V: int, n_alpha: int) -> int:
-    return int(lib().ll_steer_sweep_workspace_bytes(ll_shape(N, d, V), n_alpha))
+def ll_steer_sweep_workspace_bytes(N: int, d: int, V: int, n_alpha: int, k: int = 1) -> int:
+    if k == 1:
+        return int(lib().ll_steer_sweep_workspace_bytes(ll_shape(N, d, V), n_alpha))
+    return int(lib().ll_steer_sweep_topk_workspace_bytes(ll_shape(N, d, V), n_alpha, k))
 
 
-def ll_steer_sweep(hidden, gamma, W_U, eps, v, alphas, target_ids=None, *, workspace=None, stream=None):
+def ll_steer_sweep(hidden, gamma, W_U, eps, v, alphas, target_ids=None, *, k=None, workspace=None, stream=None):
     """Lens read-out of the steered rows RMSNorm(hidden) + alpha v for every alpha of the list in one pass over
     W_U (paper Eq. 3 / Sec. 3.4).  v [d] fp32 on the GPU, alphas a sequence of at most LL_SWEEP_MAX floats.
 
-    Returns (top1_ids [A,N] int32, top1_p [A,N] fp32, target_logp [A,N] fp32 or None, entropy [A,N] fp32).
+    Returns (top1_ids [A,N] int32, top1_p [A,N] fp32, target_logp [A,N] fp32 or None, entropy [A,N] fp32);
+    with k given (1..LL_SWEEP_KMAX, through ll_steer_sweep_topk) the first two are [A,N,k] lists.
     """
     d = hidden.shape[-1]
     h2 = hidden.reshape(-1, d)
@@ -273,20 +283,25 @@ def ll_steer_sweep(hidden, gamma, W_U, eps, v, alphas, target_ids=None, *, works
     if target_ids is not None:
         _check(target_ids, torch.int32, "target_ids", (N,))
     shape = ll_shape(N, d, V)
-    need = int(lib().ll_steer_sweep_workspace_bytes(shape, A))
+    need = ll_steer_sweep_workspace_bytes(N, d, V, A, 1 if k is None else int(k))
     if workspace is None:
         workspace = _scratch(need, hidden.device, stream)
     dev = hidden.device
-    ids = torch.empty((A, N), dtype=torch.int32, device=dev)
-    p = torch.empty((A, N), dtype=torch.float32, device=dev)
+    ids = torch.empty((A, N) if k is None else (A, N, int(k)), dtype=torch.int32, device=dev)
+    p = torch.empty((A, N) if k is None else (A, N, int(k)), dtype=torch.float32, device=dev)
     logp = torch.empty((A, N), dtype=torch.float32, device=dev) if target_ids is not None else None
     ent = torch.empty((A, N), dtype=torch.float32, device=dev)
     al = (c_float * max(A, 1))(*[float(x) for x in alphas])
-    rc = lib().ll_steer_sweep(shape, _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(h2), _ptr(gamma),
-                              _ptr(W_U), float(eps), _ptr(v), al, A, _ptr(target_ids), _ptr(ids), _ptr(p), _ptr(logp),
-                              _ptr(ent), _stream(stream))
+    if k is None:
+        rc = lib().ll_steer_sweep(shape, _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(h2), _ptr(gamma),
+                                  _ptr(W_U), float(eps), _ptr(v), al, A, _ptr(target_ids), _ptr(ids), _ptr(p), _ptr(logp),
+                                  _ptr(ent), _stream(stream))
+    else:
+        rc = lib().ll_steer_sweep_topk(shape, _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(h2),
+                                       _ptr(gamma), _ptr(W_U), float(eps), _ptr(v), al, A, int(k), _ptr(target_ids), _ptr(ids),
+                                       _ptr(p), _ptr(logp), _ptr(ent), _stream(stream))
     if rc != LL_OK:
-        raise LLError(rc, "ll_steer_sweep")
+        raise LLError(rc, "ll_steer_sweep" if k is None else "ll_steer_sweep_topk")
     return ids, p, logp, ent
 
 

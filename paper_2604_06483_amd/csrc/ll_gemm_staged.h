@@ -1,5 +1,5 @@
 // Register-staged projection kernel (any d that is a multiple of 8; RMSNorm scaling fused into the
-// A-tile load; optional bias of Eq. 1).
+// A-tile load; the epilogue is a policy as in the direct-to-LDS kernel).
 #pragma once
 
 #include "ll_epilogue.h"
@@ -15,7 +15,7 @@ namespace {
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ int lds_off(int row, int chunk) { return (row * 8 + (chunk ^ ((row >> 1) & 7))) * 16; }
 
-template <int KR, bool BIAS>
+template <class EPI>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void ll_lens_gemm_kernel(const GemmArgs p) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -57,9 +57,8 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
 
   // --- epilogue state: this lane owns lens row (rb*BN + tid).
   const int my_row = rb * BN + tid;
-  RowState<KR> st;
-  st.init();
-  st.tgt = (p.target != nullptr && my_row < p.rows) ? p.target[my_row] : -1;
+  typename EPI::State st;
+  EPI::init(st, p, my_row);
 
   const int KT = (d + BK - 1) / BK;
 
@@ -130,9 +129,9 @@ void ll_lens_gemm_kernel(const GemmArgs p) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
       }
     }
-    epilogue_tile<KR, BIAS, f32x16[8][2]>(acc, st, v0, V, p.bias);
+    EPI::tile(acc, st, v0, p, my_row);
   }
-  epilogue_store(p, st, my_row, split);
+  EPI::store(p, st, my_row, split);
 }
 
 }  // namespace

@@ -320,6 +320,74 @@ __global__ __launch_bounds__(256) void ll_sweep_merge_kernel(const float4* __res
   }
 }
 
+// The sweep with top-k lists: per (row, alpha) the splits' statistics and sorted lists of SWEEP_KS
+// entries are merged as in ll_merge_kernel (one wavefront per row, lane s = split s; the lists
+// are short, so their heads are read from the workspace directly).  Outputs are [n_alpha, N, k].
+__global__ __launch_bounds__(256) void ll_sweep_topk_merge_kernel(const float4* __restrict__ stats, const uint2* __restrict__ top,
+                                                                  const float* __restrict__ ztgt, const float* __restrict__ au,
+                                                                  int au_stride, int rows, int splits, int n_alpha, int k, int V,
+                                                                  const int32_t* __restrict__ target, int64_t out_stride,
+                                                                  int32_t* __restrict__ out_ids, float* __restrict__ out_p,
+                                                                  float* __restrict__ out_logp, float* __restrict__ out_entropy) {
+  const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const bool live = lane < splits;
+  int t = -1;
+  float zt0 = -INFINITY;
+  if (target != nullptr) {
+    t = target[row];
+    zt0 = wave_max(live ? ztgt[(int64_t)row * splits + lane] : -INFINITY);
+  }
+  const bool t_ok = t >= 0 && t < V;
+  int width = 1;
+  while (width < splits) width <<= 1;
+  for (int a = 0; a < n_alpha; ++a) {
+    const int64_t part = ((int64_t)row * splits + (live ? lane : 0)) * n_alpha + a;
+    float4 q = make_float4(-INFINITY, 0.f, 0.f, 0.f);
+    if (live) q = stats[part];
+    const float M = wave_max(q.x);
+    const float sc = live ? __builtin_amdgcn_exp2f((q.x - M) * LOG2E) : 0.f;
+    const float S = wave_sum(sc * q.y);
+    const float T = wave_sum(sc * q.z);
+    const float logS = logf(S);
+    const int64_t o = (int64_t)a * out_stride + row;
+    if (lane == 0) {
+      out_entropy[o] = (M - T / S) + logS;
+      if (target != nullptr)
+        out_logp[o] = t_ok ? ((zt0 + au[(int64_t)a * au_stride + t]) - M) - logS : __builtin_nanf("");
+    }
+    const uint2* tl = top + part * SWEEP_KS;
+    int head = 0;
+    float z = -INFINITY;
+    int id = INT_MAX;
+    if (live) {
+      const uint2 e = tl[0];
+      z = __uint_as_float(e.x);
+      id = (int)e.y;
+    }
+    for (int j = 0; j < k; ++j) {
+      const float bz = group_max(z, width);
+      const int bi = group_min_int(z == bz ? id : INT_MAX, width);
+      if (live && z == bz && id == bi) {
+        ++head;
+        if (head < SWEEP_KS) {
+          const uint2 e = tl[head];
+          z = __uint_as_float(e.x);
+          id = (int)e.y;
+        } else {
+          z = -INFINITY;
+          id = INT_MAX;
+        }
+      }
+      if (lane == 0) {
+        out_ids[o * k + j] = bi;
+        out_p[o * k + j] = __builtin_amdgcn_exp2f(((bz - M) - logS) * LOG2E);
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
@@ -417,7 +485,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   void (*kern)(const GemmArgs);
 #define LL_PICK(KR) \
   (dma ? (bias ? ll_lens_gemm_dma_kernel<TopKEpilogue<KR, true>> : ll_lens_gemm_dma_kernel<TopKEpilogue<KR, false>>) \
-       : (bias ? ll_lens_gemm_kernel<KR, true> : ll_lens_gemm_kernel<KR, false>))
+       : (bias ? ll_lens_gemm_kernel<TopKEpilogue<KR, true>> : ll_lens_gemm_kernel<TopKEpilogue<KR, false>>))
   if (k <= 4)
     kern = LL_PICK(4);
   else if (k <= 12)
@@ -544,12 +612,13 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
 }
 
 struct SweepPlan {
-  size_t off_au, off_stats, off_ztgt, off_panel, total;
+  size_t off_au, off_stats, off_ztgt, off_top, off_inv_rms, off_panel, total;
   int64_t lda;
   int au_stride;
 };
 
-SweepPlan make_sweep_plan(const ll_shape* s, int n_alpha) {
+// k == 1: the arg max travels inside the statistics; k > 1: room for the sorted lists as well.
+SweepPlan make_sweep_plan(const ll_shape* s, int n_alpha, int k = 1) {
   SweepPlan p;
   size_t off = 0;
   p.au_stride = (s->V + BM - 1) / BM * BM;
@@ -561,22 +630,28 @@ SweepPlan make_sweep_plan(const ll_shape* s, int n_alpha) {
   off = align_up(off + partials * (size_t)n_alpha * sizeof(float4), 256);
   p.off_ztgt = off;
   off = align_up(off + partials * sizeof(float), 256);
+  p.off_top = off;
+  if (k > 1) off = align_up(off + partials * (size_t)SWEEP_TOPK_ALPHAS * SWEEP_KS * sizeof(uint2), 256);
+  p.off_inv_rms = off;   // d not a multiple of 64: the register-staged kernel normalises inside its A-tile load
+  off = align_up(off + rows * sizeof(float), 256);
   p.lda = s->d;
-  p.off_panel = off;
+  p.off_panel = off;     // d a multiple of 64: normalised rows for the direct-to-LDS kernel
   off = align_up(off + rows * (size_t)p.lda * sizeof(uint16_t), 256);
   p.total = off;
   return p;
 }
 
-bool sweep_shape_ok(const ll_shape* s, int n_alpha) {
-  return shape_ok(s, 1) && s->d % DK == 0 && n_alpha >= 1 && n_alpha <= SWEEP_MAX &&
-         (int64_t)BM * s->d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * s->d * 2 < (int64_t)1 << 31;
+// The direction kernel keeps v in LDS: 4 d bytes of the 160 KB.
+constexpr int SWEEP_MAX_D = 40960;
+
+bool sweep_shape_ok(const ll_shape* s, int n_alpha, int k = 1) {
+  return shape_ok(s, k) && k <= SWEEP_KS && s->d <= SWEEP_MAX_D && n_alpha >= 1 && n_alpha <= SWEEP_MAX;
 }
 
 int sweep_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
-               const void* W_U, float eps, const float* v, const float* alphas, int n_alpha, const int32_t* target_ids,
+               const void* W_U, float eps, const float* v, const float* alphas, int n_alpha, int k, const int32_t* target_ids,
                int32_t* out_ids, float* out_p, float* out_logp, float* out_entropy, hipStream_t stream) {
-  if (!sweep_shape_ok(shape, n_alpha)) return LL_EINVAL;
+  if (!sweep_shape_ok(shape, n_alpha, k)) return LL_EINVAL;
   if (shape->N == 0) return LL_OK;
   if (hidden == nullptr || W_U == nullptr || v == nullptr || alphas == nullptr || out_ids == nullptr || out_p == nullptr ||
       out_entropy == nullptr)
@@ -589,13 +664,15 @@ int sweep_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, c
     al.a[a] = a < n_alpha ? alphas[a] : 0.f;
     if (!(al.a[a] == al.a[a]) || al.a[a] - al.a[a] != 0.f) return LL_EINVAL;   // NaN or infinite
   }
-  const SweepPlan plan = make_sweep_plan(shape, n_alpha);
+  const SweepPlan plan = make_sweep_plan(shape, n_alpha, k);
   if (workspace == nullptr || workspace_bytes < plan.total || ((uintptr_t)workspace & 255)) return LL_EWORKSPACE;
 
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   float* au = reinterpret_cast<float*>(ws + plan.off_au);
   float4* stats = reinterpret_cast<float4*>(ws + plan.off_stats);
   float* ztgt = reinterpret_cast<float*>(ws + plan.off_ztgt);
+  uint2* top = reinterpret_cast<uint2*>(ws + plan.off_top);
+  float* inv_rms = reinterpret_cast<float*>(ws + plan.off_inv_rms);
   uint16_t* panel = reinterpret_cast<uint16_t*>(ws + plan.off_panel);
   const int64_t N = shape->N;
   const int d = shape->d, V = shape->V;
@@ -614,17 +691,28 @@ int sweep_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, c
                          plan.au_stride - V, 0.f);
     LL_CHECK_S(hipGetLastError());
   }
+  if ((size_t)d * sizeof(float) > 64 * 1024)
+    if (const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(ll_unembed_direction_kernel), (size_t)d * sizeof(float));
+        rc != LL_OK)
+      return rc;
   hipLaunchKernelGGL(ll_unembed_direction_kernel, dim3(NUM_CU * 4), dim3(256), (size_t)d * sizeof(float), stream,
                      static_cast<const uint16_t*>(W_U), v, V, d, al, n_alpha, au, plan.au_stride);
   LL_CHECK_S(hipGetLastError());
-  auto kern = ll_lens_gemm_dma_kernel<SweepEpilogue>;
-  const size_t lds = (size_t)SLOTS * SLOT_BYTES;
+  // The direct-to-LDS kernel needs whole K stages of 64 and 32-bit row offsets; otherwise the register-staged
+  // kernel, which normalises inside its A-tile load.
+  const bool dma = d % DK == 0 && (int64_t)BM * d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * d * 2 < (int64_t)1 << 31;
+  void (*kern)(const GemmArgs);
+  if (k == 1)
+    kern = dma ? ll_lens_gemm_dma_kernel<SweepEpilogue> : ll_lens_gemm_kernel<SweepEpilogue>;
+  else
+    kern = dma ? ll_lens_gemm_dma_kernel<SweepTopKEpilogue> : ll_lens_gemm_kernel<SweepTopKEpilogue>;
+  const size_t lds = dma ? (size_t)SLOTS * SLOT_BYTES : (size_t)(BM + BN) * BK * 2;
   if (const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds); rc != LL_OK) return rc;
 
   for (int64_t r0 = 0; r0 < N; r0 += CHUNK_ROWS) {
     const int rows = (int)((N - r0 < CHUNK_ROWS) ? (N - r0) : CHUNK_ROWS);
     const uint16_t* h_rows = static_cast<const uint16_t*>(hidden) + r0 * d;
-    if (gamma != nullptr) {
+    if (gamma != nullptr && dma) {
       const dim3 grid((unsigned)((rows + 3) / 4));
       const uint16_t* g = static_cast<const uint16_t*>(gamma);
       if (d <= 64 * 8 * 4)
@@ -634,6 +722,10 @@ int sweep_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, c
       else
         hipLaunchKernelGGL(ll_norm_panel_kernel<0>, grid, dim3(256), 0, stream, h_rows, g, panel, rows, d, plan.lda, eps);
       LL_CHECK_S(hipGetLastError());
+    } else if (gamma != nullptr) {
+      hipLaunchKernelGGL(ll_rms_stats_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, h_rows, (int64_t)rows, d,
+                         eps, inv_rms);
+      LL_CHECK_S(hipGetLastError());
     }
     const int row_blocks = (rows + BN - 1) / BN;
     int splits = NUM_CU / row_blocks;
@@ -641,8 +733,11 @@ int sweep_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, c
     if (splits > tiles) splits = tiles;
     if (splits < 1) splits = 1;
     GemmArgs a = {};
-    a.A = gamma != nullptr ? panel : h_rows;
+    a.A = (gamma != nullptr && dma) ? panel : h_rows;
     a.lda = plan.lda;
+    a.inv_rms = (gamma != nullptr && !dma) ? inv_rms : nullptr;
+    a.gamma = static_cast<const uint16_t*>(gamma);
+    a.sweep_top = top;
     a.W = static_cast<const uint16_t*>(W_U);
     a.target = target_ids ? target_ids + r0 : nullptr;
     a.rows = rows;
@@ -652,18 +747,30 @@ int sweep_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, c
     a.splits = splits;
     a.tiles = tiles;
     a.row_blocks = row_blocks;
-    a.au = au;
     a.au_stride = plan.au_stride;
-    a.n_alpha = n_alpha;
     a.sweep_stats = stats;
     a.sweep_ztgt = ztgt;
     const int grid = (row_blocks * splits + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHREADS), lds, stream, a);
-    LL_CHECK_S(hipGetLastError());
-    hipLaunchKernelGGL(ll_sweep_merge_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, (const float4*)stats,
-                       (const float*)ztgt, (const float*)au, plan.au_stride, rows, splits, n_alpha, V, a.target, N,
-                       out_ids + r0, out_p + r0, out_logp ? out_logp + r0 : nullptr, out_entropy + r0);
-    LL_CHECK_S(hipGetLastError());
+    // k == 1: all alphas in one pass over W_U; with lists: SWEEP_TOPK_ALPHAS alphas per pass
+    const int per_pass = k == 1 ? n_alpha : SWEEP_TOPK_ALPHAS;
+    for (int a0 = 0; a0 < n_alpha; a0 += per_pass) {
+      const int na = n_alpha - a0 < per_pass ? n_alpha - a0 : per_pass;
+      a.au = au + (size_t)a0 * plan.au_stride;
+      a.n_alpha = na;
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHREADS), lds, stream, a);
+      LL_CHECK_S(hipGetLastError());
+      const int64_t o0 = (int64_t)a0 * N + r0;   // first output of this pass: alpha a0, row r0
+      if (k == 1)
+        hipLaunchKernelGGL(ll_sweep_merge_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, (const float4*)stats,
+                           (const float*)ztgt, (const float*)a.au, plan.au_stride, rows, splits, na, V, a.target, N,
+                           out_ids + o0, out_p + o0, out_logp ? out_logp + o0 : nullptr, out_entropy + o0);
+      else   // outputs [n_alpha, N, k]
+        hipLaunchKernelGGL(ll_sweep_topk_merge_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, (const float4*)stats,
+                           (const uint2*)top, (const float*)ztgt, (const float*)a.au, plan.au_stride, rows, splits, na, k, V,
+                           a.target, N, out_ids + o0 * k, out_p + o0 * k, out_logp ? out_logp + o0 : nullptr,
+                           out_entropy + o0);
+      LL_CHECK_S(hipGetLastError());
+    }
   }
 #undef LL_CHECK_S
   return LL_OK;
@@ -730,10 +837,23 @@ size_t ll_steer_sweep_workspace_bytes(const ll_shape* shape, int n_alpha) {
   return make_sweep_plan(shape, n_alpha).total;
 }
 
+size_t ll_steer_sweep_topk_workspace_bytes(const ll_shape* shape, int n_alpha, int k) {
+  if (!sweep_shape_ok(shape, n_alpha, k)) return 0;
+  return make_sweep_plan(shape, n_alpha, k).total;
+}
+
+int ll_steer_sweep_topk(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
+                        const void* W_U, float eps, const float* v, const float* alphas, int n_alpha, int k,
+                        const int32_t* target_ids, int32_t* out_topk_ids, float* out_topk_p, float* out_target_logp,
+                        float* out_entropy, void* stream) {
+  return sweep_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, eps, v, alphas, n_alpha, k, target_ids, out_topk_ids,
+                    out_topk_p, out_target_logp, out_entropy, static_cast<hipStream_t>(stream));
+}
+
 int ll_steer_sweep(const ll_shape* shape, void* workspace, size_t workspace_bytes, const void* hidden, const void* gamma,
                    const void* W_U, float eps, const float* v, const float* alphas, int n_alpha, const int32_t* target_ids,
                    int32_t* out_top1_ids, float* out_top1_p, float* out_target_logp, float* out_entropy, void* stream) {
-  return sweep_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, eps, v, alphas, n_alpha, target_ids, out_top1_ids,
+  return sweep_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, eps, v, alphas, n_alpha, 1, target_ids, out_top1_ids,
                     out_top1_p, out_target_logp, out_entropy, static_cast<hipStream_t>(stream));
 }
 

@@ -174,7 +174,14 @@ def test_steer_sweep_rejects_bad_arguments_before_any_device_work():
     s = LL.ll_shape(16, 64, 300)
     need = LL.ll_steer_sweep_workspace_bytes(16, 64, 300, 9)
     assert need > 0 and need % 256 == 0
-    assert LL.ll_steer_sweep_workspace_bytes(16, 72, 300, 9) == 0        # d not a multiple of 64
+    assert LL.ll_steer_sweep_workspace_bytes(16, 72, 300, 9) > 0         # any multiple of 8 (the register-staged kernel)
+    assert LL.ll_steer_sweep_workspace_bytes(16, 76, 300, 9) == 0        # d not a multiple of 8
+    assert LL.ll_steer_sweep_workspace_bytes(16, 40960, 300, 9) > 0      # the largest hidden size: v is held in LDS
+    assert LL.ll_steer_sweep_workspace_bytes(16, 40968, 300, 9) == 0
+    # lists of up to LL_SWEEP_KMAX tokens per alpha cost workspace; longer lists are refused
+    assert LL.ll_steer_sweep_workspace_bytes(16, 64, 300, 9, 3) > need
+    assert LL.ll_steer_sweep_workspace_bytes(16, 64, 300, 9, LL.LL_SWEEP_KMAX + 1) == 0
+    assert LL.ll_steer_sweep_workspace_bytes(16, 64, 2, 9, 3) == 0       # k > V
     assert LL.ll_steer_sweep_workspace_bytes(16, 64, 300, 0) == 0
     assert LL.ll_steer_sweep_workspace_bytes(16, 64, 300, LL.LL_SWEEP_MAX + 1) == 0
     # the table of alpha * (W_U v) is part of the workspace: more alphas, more bytes
@@ -184,7 +191,8 @@ def test_steer_sweep_rejects_bad_arguments_before_any_device_work():
                                            for k in ("shape", "ws", "wsb", "h", "g", "w", "eps", "v", "al", "n", "t", "ids",
                                                      "p", "lp", "e", "st")])
     for bad in (dict(h=None), dict(w=None), dict(v=None), dict(al=None), dict(ids=None), dict(p=None), dict(e=None),
-                dict(lp=None), dict(n=0), dict(n=10), dict(eps=-1.0), dict(shape=LL.ll_shape(16, 72, 300)),
+                dict(lp=None), dict(n=0), dict(n=10), dict(eps=-1.0), dict(shape=LL.ll_shape(16, 76, 300)),
+                dict(shape=LL.ll_shape(16, 40968, 300)),
                 dict(v=_fake((1 << 20) + 4))):
         assert call(**bad) == LL.LL_EINVAL, bad
     nan = (ctypes.c_float * 9)(*([0.0] * 8 + [float("nan")]))
@@ -192,6 +200,11 @@ def test_steer_sweep_rejects_bad_arguments_before_any_device_work():
     assert call(ws=None) == LL.LL_EWORKSPACE
     assert call(wsb=1024) == LL.LL_EWORKSPACE
     assert call(shape=LL.ll_shape(0, 64, 300), h=None, w=None, ws=None, wsb=0) == LL.LL_OK
+    # the variant with lists: k out of range
+    topk = lambda k: L.ll_steer_sweep_topk(s, _fake(4096 * 256), 1 << 30, f, f, f, 1e-5, f, al, 9, k, f, f, f, f, f, None)
+    assert topk(0) == LL.LL_EINVAL and topk(LL.LL_SWEEP_KMAX + 1) == LL.LL_EINVAL
+    m = re.search(r"#define\s+LL_SWEEP_KMAX\s+(\d+)", open(HEADER).read())
+    assert m and int(m.group(1)) == LL.LL_SWEEP_KMAX
 
 
 def test_inject_raw_and_capture_append_reject_bad_arguments():

@@ -41,7 +41,7 @@ def kernel_bodies(asm_text, needle):
 
 def test_m0_is_only_written_by_the_lds_base_setter(asm):
     bodies = kernel_bodies(asm, "ll_lens_gemm_dma_kernel")
-    assert len(bodies) == 9, sorted(bodies)          # four top-k list lengths, each with and without a bias, and the steering sweep
+    assert len(bodies) == 10, sorted(bodies)         # four top-k list lengths, each with and without a bias, and the two steering sweeps
     for name, ins in bodies.items():
         loads = [i for i, l in enumerate(ins) if l.startswith("global_load_lds_dwordx4")]
         assert len(loads) >= 16 + 36, (name, len(loads))          # main loop + prologue
@@ -65,7 +65,7 @@ def test_projection_kernels_fit_one_wave_per_simd_without_scratch(asm):
         meta[m.group(1)] = dict(vgpr=get("vgpr_count"), scratch=get("private_segment_fixed_size"),
                                 vspill=get("vgpr_spill_count"))
     dma = {k: v for k, v in meta.items() if "ll_lens_gemm_dma_kernel" in k}
-    assert len(dma) == 9
+    assert len(dma) == 10
     for name, v in dma.items():
         assert v["vgpr"] <= 512 and v["scratch"] == 0 and v["vspill"] == 0, (name, v)
 

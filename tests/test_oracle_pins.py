@@ -346,6 +346,22 @@ def pin_steer_sweep(O):
             assert abs(got["top1_p"][ai, r] - want["p"][0]) < 1e-12
             assert abs(got["entropy"][ai, r] - want["entropy"]) < 1e-12
             assert abs(got["target_logp"][ai, r] - want["target_logp"]) < 1e-12
+    # the k most likely tokens per alpha (the paper's figures list three per cell): brute force again, every rank
+    got3 = O.steer_sweep(h, g, W, 1e-5, v, alphas, t, k=3)
+    assert got3["topk_ids"].shape == (4, 3, 3) and got3["topk_p"].shape == (4, 3, 3)
+    for ai, al in enumerate(alphas):
+        for r in range(3):
+            ms = math.fsum(x * x for x in hf[r]) / 8
+            a = [BF.round_to_bf16(gf[j] * hf[r][j] / math.sqrt(ms + 1e-5)) for j in range(8)]
+            want = BF.project_row([a[j] + al * float(v[j]) for j in range(8)], None, [list(w) for w in Wf], 1e-5, 3, int(t[r]))
+            assert list(got3["topk_ids"][ai, r]) == want["ids"]
+            assert max(abs(got3["topk_p"][ai, r, i] - want["p"][i]) for i in range(3)) < 1e-12
+    assert np.array_equal(got3["top1_ids"], got["top1_ids"]) and np.array_equal(got3["topk_ids"][:, :, 0], got["top1_ids"])
+    np.testing.assert_array_equal(got3["entropy"], got["entropy"])           # the list length changes nothing else
+    assert np.all(np.diff(got3["topk_p"], axis=2) <= 0)
+    base3 = O.lens_project(h, g, W, 1e-5, 3, t)
+    assert np.array_equal(got3["topk_ids"][1], base3["topk_ids"])              # alpha = 0: the plain projection's list
+    np.testing.assert_allclose(got3["topk_p"][1], base3["topk_p"], rtol=1e-13)
     # alpha = 0 is the plain projection
     base = O.lens_project(h, g, W, 1e-5, 1, t)
     assert np.array_equal(got["top1_ids"][1], base["topk_ids"][:, 0])
@@ -531,9 +547,9 @@ def _inject_variant(kind):
 
 
 def _sweep_variant(kind):
-    def f(hidden_bits, gamma_bits, w_bits, eps, v, alphas, target_ids=None, round_a=True):
+    def f(hidden_bits, gamma_bits, w_bits, eps, v, alphas, target_ids=None, round_a=True, k=1):
         if kind == "minus":
-            return _real["steer_sweep"](hidden_bits, gamma_bits, w_bits, eps, v, [-x for x in alphas], target_ids, round_a)
+            return _real["steer_sweep"](hidden_bits, gamma_bits, w_bits, eps, v, [-x for x in alphas], target_ids, round_a, k)
         if kind == "rounds_steered_rows":   # what inject + project does, not what the sweep is defined as
             outs = []
             for al in alphas:
@@ -543,11 +559,19 @@ def _sweep_variant(kind):
                 else:
                     a = _real["rmsnorm"](hidden_bits, gamma_bits, eps, round_a=True) + al * np.asarray(v, np.float64)[None, :]
                     bits = _real["f64_to_bf16_bits"](a)
-                outs.append(_real["lens_project"](bits, None, w_bits, eps, 1, target_ids))
+                outs.append(_real["lens_project"](bits, None, w_bits, eps, k, target_ids))
             return {"top1_ids": np.stack([o["topk_ids"][:, 0] for o in outs]), "top1_p": np.stack([o["topk_p"][:, 0] for o in outs]),
+                    "topk_ids": np.stack([o["topk_ids"] for o in outs]), "topk_p": np.stack([o["topk_p"] for o in outs]),
+                    "topk_logits": np.stack([o["topk_logits"] for o in outs]),
                     "target_logp": np.stack([o["target_logp"] for o in outs]), "entropy": np.stack([o["entropy"] for o in outs])}
         if kind == "unnormalised_rows":     # steering added to the raw hidden state
-            return _real["steer_sweep"](hidden_bits, None, w_bits, eps, v, alphas, target_ids, round_a)
+            return _real["steer_sweep"](hidden_bits, None, w_bits, eps, v, alphas, target_ids, round_a, k)
+        if kind == "lists_of_unsteered_logits":   # statistics per alpha, but every alpha lists the tokens of alpha = 0
+            out = _real["steer_sweep"](hidden_bits, gamma_bits, w_bits, eps, v, alphas, target_ids, round_a, k)
+            zero = _real["steer_sweep"](hidden_bits, gamma_bits, w_bits, eps, v, [0.0], target_ids, round_a, k)
+            for key in ("topk_ids", "topk_p", "topk_logits"):
+                out[key] = np.repeat(zero[key], len(alphas), axis=0)
+            return out
     return f
 
 
@@ -599,6 +623,7 @@ MUTANTS = {
     "sweep_minus": dict(steer_sweep=_sweep_variant("minus")),
     "sweep_rounds_steered_rows": dict(steer_sweep=_sweep_variant("rounds_steered_rows")),
     "sweep_unnormalised_rows": dict(steer_sweep=_sweep_variant("unnormalised_rows")),
+    "sweep_lists_of_unsteered_logits": dict(steer_sweep=_sweep_variant("lists_of_unsteered_logits")),
     "inject_raw_scale_after_clip": dict(steer_inject_raw=_inject_raw_variant("scale_after_clip")),
     "inject_raw_clip_to_rms": dict(steer_inject_raw=_inject_raw_variant("clip_to_rms")),
     "inject_raw_sign_lost": dict(steer_inject_raw=_inject_raw_variant("sign_lost")),
