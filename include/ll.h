@@ -83,9 +83,18 @@ int ll_project(const ll_shape* shape, void* workspace, size_t workspace_bytes,
  *   flags  LL_FLAG_TOPK_SOFTMAX: out_topk_p holds the softmax over the k selected logits only
  *          (paper Sec. 3.3, "Top-k extraction": a conditional distribution over the candidates),
  *          i.e. p_i / sum_{j in top-k} p_j; entropy and target log-prob stay full-vocabulary.
+ *          LL_FLAG_REGISTER_STAGED: run this call on the register-staged kernel, which applies the
+ *          RMSNorm scaling inside the A-tile load of the GEMM, even where the default applies (the
+ *          direct-to-LDS kernel fed from a normalised bf16 panel written once per row pass; d a
+ *          multiple of 64).  Both compute the same quantities from the same bf16 operands (the
+ *          normalised row is rounded to bf16 identically); they use different MFMA shapes, so a
+ *          logit's fp32 partial sums are added in a different order and results agree to fp32
+ *          accumulation rounding.  For tuning and tests; any d that is not a multiple of 64 runs on
+ *          this kernel anyway.
  *          Any other bit set is LL_EINVAL.
  */
-#define LL_FLAG_TOPK_SOFTMAX 1u
+#define LL_FLAG_TOPK_SOFTMAX    1u
+#define LL_FLAG_REGISTER_STAGED 2u
 int ll_project_ex(const ll_shape* shape, void* workspace, size_t workspace_bytes,
                   const void* hidden, const void* gamma, const void* W_U, const float* bias,
                   unsigned flags, float eps, int k, const int32_t* target_ids,
@@ -258,19 +267,6 @@ int ll_steer_sweep_topk(const ll_shape* shape, void* workspace, size_t workspace
                         const float* v, const float* alphas, int n_alpha, int k, const int32_t* target_ids,
                         int32_t* out_topk_ids, float* out_topk_p, float* out_target_logp, float* out_entropy,
                         void* stream);
-
-/*
- * Chooses the projection kernel for ll_project calls of this process that start afterwards
- * (one process-wide setting; a call already running keeps the kernel it chose):
- *   0  automatic (default)
- *   1  register-staged kernel: the RMSNorm scaling is applied inside the A-tile load of the GEMM
- *   2  direct-to-LDS kernel fed from a normalised bf16 panel written once per row pass
- * Both compute the same quantities from the same bf16 operands (the normalised row is rounded
- * to bf16 identically); they use different MFMA shapes, so a logit's fp32 partial sums are
- * added in a different order and results agree to fp32 accumulation rounding.  For tuning
- * and tests.  Returns LL_EINVAL for any other value.
- */
-int ll_set_gemm_path(int path);
 
 /* Text for an LL_E* code (static storage, never NULL). */
 const char* ll_error_string(int code);

@@ -4,7 +4,7 @@
 ll_project_ex (through ll_project's bias / topk_softmax arguments), ll_project_timed (timed=True),
 ll_project_static and ll_project_static_pass_rows, ll_steer_workspace_bytes, ll_steer_vector,
 ll_steer_inject, ll_steer_inject_raw, ll_steer_sweep_workspace_bytes, ll_steer_sweep and
-ll_steer_sweep_topk (k=...), ll_capture_append, ll_set_gemm_path, ll_error_string and
+ll_steer_sweep_topk (k=...), ll_capture_append, ll_error_string and
 ll_last_hip_error (inside LLError).  `workloads` draws the seeded synthetic inputs; `serialize`
 writes the paper's JSON output.  Nothing is loaded at import time: the shared library is opened
 on first use and its absence is an error, never a fallback.

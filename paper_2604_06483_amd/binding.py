@@ -16,6 +16,7 @@ LL_OK, LL_EINVAL, LL_EWORKSPACE, LL_EHIP, LL_ESCRATCH = 0, -1, -2, -3, -4
 LL_KMAX = 32
 LL_STATIC_SCRATCH_BYTES = 64 << 20
 LL_FLAG_TOPK_SOFTMAX = 1
+LL_FLAG_REGISTER_STAGED = 2
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libll.so")
 _lib = None
@@ -85,8 +86,6 @@ def lib() -> ctypes.CDLL:
         L.ll_steer_inject_raw.restype = c_int
         L.ll_capture_append.argtypes = [POINTER(ll_capture_shape), c_void_p, c_void_p, c_int64, c_int64, c_void_p]
         L.ll_capture_append.restype = c_int
-        L.ll_set_gemm_path.argtypes = [c_int]
-        L.ll_set_gemm_path.restype = c_int
         L.ll_error_string.argtypes = [c_int]
         L.ll_error_string.restype = c_char_p
         L.ll_last_hip_error.argtypes = []
@@ -121,12 +120,6 @@ def _scratch(nbytes, device, stream):
     return ws
 
 
-def ll_set_gemm_path(path: int) -> None:
-    rc = lib().ll_set_gemm_path(int(path))
-    if rc != LL_OK:
-        raise LLError(rc, "ll_set_gemm_path")
-
-
 def ll_workspace_bytes(N: int, d: int, V: int, k: int) -> int:
     return int(lib().ll_workspace_bytes(ll_shape(N, d, V), k))
 
@@ -136,10 +129,11 @@ def ll_steer_workspace_bytes(d: int) -> int:
 
 
 def ll_project(hidden, gamma, W_U, eps, k, target_ids=None, *, workspace=None, stream=None, out=None, timed=False,
-               bias=None, topk_softmax=False):
+               bias=None, topk_softmax=False, register_staged=False):
     """hidden [..., d] bf16, gamma [d] bf16 or None, W_U [V, d] bf16, target_ids [N] int32 or None.
-    bias [V] fp32 (the b of Eq. 1) and topk_softmax (probabilities over the k selected logits only, the paper's
-    own output format) go through ll_project_ex.
+    bias [V] fp32 (the b of Eq. 1), topk_softmax (probabilities over the k selected logits only, the paper's
+    own output format) and register_staged (the kernel with the norm inside its A-tile load) go through
+    ll_project_ex.
 
     Returns (topk_ids [N,k] int32, topk_p [N,k] fp32, target_logp [N] fp32 or None, entropy [N] fp32),
     plus the three phase times in ms when timed=True (that variant synchronises the stream).
@@ -168,12 +162,13 @@ def ll_project(hidden, gamma, W_U, eps, k, target_ids=None, *, workspace=None, s
         ids, p, logp, ent = out
     args = [shape, _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(h2), _ptr(gamma), _ptr(W_U),
             float(eps), int(k), _ptr(target_ids), _ptr(ids), _ptr(p), _ptr(logp), _ptr(ent), _stream(stream)]
-    if bias is not None or topk_softmax:
+    if bias is not None or topk_softmax or register_staged:
         if timed:
-            raise ValueError("the timed variant has no bias / top-k-softmax form")
+            raise ValueError("the timed variant has no bias / top-k-softmax / kernel-choice form")
         if bias is not None:
             _check(bias, torch.float32, "bias", (V,))
-        rc = lib().ll_project_ex(*args[:6], _ptr(bias), LL_FLAG_TOPK_SOFTMAX if topk_softmax else 0, *args[6:])
+        flags = (LL_FLAG_TOPK_SOFTMAX if topk_softmax else 0) | (LL_FLAG_REGISTER_STAGED if register_staged else 0)
+        rc = lib().ll_project_ex(*args[:6], _ptr(bias), flags, *args[6:])
         if rc != LL_OK:
             raise LLError(rc, "ll_project_ex")
         return ids, p, logp, ent

@@ -427,10 +427,6 @@ Plan make_plan(const ll_shape* s, int k, int chunk_rows = CHUNK_ROWS) {
   return p;
 }
 
-// 0: automatic; 1: register-staged kernel with the norm fused into the A-tile load; 2: direct-to-LDS
-// kernel fed from a normalised panel.
-std::atomic<int> g_gemm_path{0};
-
 // A kernel that uses more than 64 KB of dynamic LDS has to be told so once per device; remembered
 // here so that the hot path makes no attribute call.
 int allow_dynamic_lds(const void* kern, size_t lds) {
@@ -460,7 +456,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     return LL_EINVAL;
   if (target_ids != nullptr && out_target_logp == nullptr) return LL_EINVAL;
   if (!(eps >= 0.f)) return LL_EINVAL;
-  if ((flags & ~(unsigned)LL_FLAG_TOPK_SOFTMAX) != 0 || ((uintptr_t)bias & 3)) return LL_EINVAL;
+  if ((flags & ~(unsigned)(LL_FLAG_TOPK_SOFTMAX | LL_FLAG_REGISTER_STAGED)) != 0 || ((uintptr_t)bias & 3)) return LL_EINVAL;
   const uintptr_t align_or = (uintptr_t)hidden | (uintptr_t)W_U | (uintptr_t)gamma;
   if (align_or & 15) return LL_EINVAL;
   const Plan plan = make_plan(shape, k, chunk_rows);
@@ -479,7 +475,7 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
   const bool dma_ok = d % DK == 0 && (int64_t)BM * d * 2 < (int64_t)1 << 31 && (int64_t)CHUNK_ROWS * plan.lda * 2 < (int64_t)1 << 31;
   // A bias (rare: the paper's model families have none) selects a separate instantiation of the
   // kernel, so that calls without one carry no code or registers for it.
-  const bool dma = g_gemm_path.load(std::memory_order_relaxed) != 1 && dma_ok;
+  const bool dma = dma_ok && !(flags & LL_FLAG_REGISTER_STAGED);
   const size_t lds = dma ? (size_t)SLOTS * SLOT_BYTES : (size_t)(BM + BN) * BK * 2;
   // The top-k lists live in registers: the kernels are built for a few list lengths KR >= k.
   void (*kern)(const GemmArgs);
@@ -855,12 +851,6 @@ int ll_steer_sweep(const ll_shape* shape, void* workspace, size_t workspace_byte
                    int32_t* out_top1_ids, float* out_top1_p, float* out_target_logp, float* out_entropy, void* stream) {
   return sweep_impl(shape, workspace, workspace_bytes, hidden, gamma, W_U, eps, v, alphas, n_alpha, 1, target_ids, out_top1_ids,
                     out_top1_p, out_target_logp, out_entropy, static_cast<hipStream_t>(stream));
-}
-
-int ll_set_gemm_path(int path) {
-  if (path < 0 || path > 2) return LL_EINVAL;
-  g_gemm_path.store(path, std::memory_order_relaxed);
-  return LL_OK;
 }
 
 size_t ll_workspace_bytes(const ll_shape* shape, int k) {

@@ -142,8 +142,9 @@ def test_project_ex_rejects_unknown_flags_and_misaligned_bias():
     f = _fake()
     s = LL.ll_shape(16, 64, 300)
     args = lambda bias, flags: (s, _fake(4096 * 256), 1 << 30, f, f, f, bias, flags, 1e-5, 4, f, f, f, f, f, None)
-    assert L.ll_project_ex(*args(None, 2)) == LL.LL_EINVAL
+    assert L.ll_project_ex(*args(None, 4)) == LL.LL_EINVAL
     assert L.ll_project_ex(*args(None, 0xFFFF)) == LL.LL_EINVAL
+    assert LL.LL_FLAG_TOPK_SOFTMAX == 1 and LL.LL_FLAG_REGISTER_STAGED == 2      # the two bits that are defined
     assert L.ll_project_ex(*args(_fake((1 << 20) + 2), 0)) == LL.LL_EINVAL
     assert L.ll_project_ex(LL.ll_shape(0, 64, 300), None, 0, None, None, None, None, 1, 1e-5, 4, None, None, None, None,
                            None, None) == LL.LL_OK

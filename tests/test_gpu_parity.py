@@ -17,17 +17,28 @@ DEV = "cuda:0"
 
 
 
+STAGED = False      # set per case: the register-staged kernel (norm inside its A-tile load) instead of the default one
+
+
 @pytest.fixture(params=[2, 1], ids=["dma-panel", "fused-norm"], autouse=True)
 def gemm_path(request):
-    """Every case runs on both projection kernels."""
-    LL.ll_set_gemm_path(request.param)
+    """Every case runs on both projection kernels (2: the default; 1: LL_FLAG_REGISTER_STAGED on every call)."""
+    global STAGED
+    STAGED = request.param == 1
     yield request.param
-    LL.ll_set_gemm_path(0)
+    STAGED = False
+
+
+def project(*args, **kw):
+    """LL.ll_project on the kernel the case is parametrised with."""
+    if STAGED and not kw.get("timed"):
+        kw["register_staged"] = True
+    return LL.ll_project(*args, **kw)
 
 
 def run_project(w, k=None, gamma="w", target=True):
     cfg = w.cfg
-    res = LL.ll_project(w.hidden, w.gamma if gamma == "w" else gamma, w.W_U, cfg.eps, k or cfg.k,
+    res = project(w.hidden, w.gamma if gamma == "w" else gamma, w.W_U, cfg.eps, k or cfg.k,
                         w.target_ids if target else None)
     torch.cuda.synchronize()
     return P.to_numpy(res, has_target=target)
@@ -105,7 +116,7 @@ def test_empty_input_is_a_noop():
     say("N = 0")
     w = WL.make_workload(WL.LensConfig("e", L=1, T=4, d=64, V=300, k=3), DEV)
     empty = w.hidden.reshape(-1, 64)[:0]
-    ids, p, logp, ent = LL.ll_project(empty, w.gamma, w.W_U, 1e-5, 3, w.target_ids[:0])
+    ids, p, logp, ent = project(empty, w.gamma, w.W_U, 1e-5, 3, w.target_ids[:0])
     torch.cuda.synchronize()
     assert ids.shape == (0, 3) and ent.shape == (0,)
 
@@ -183,7 +194,7 @@ def test_no_target_and_prenormalised_rows():
     ref = oracle_for(w, np.arange(cfg.N))
     P.compare(got, ref, cfg.k, has_target=False, label="no-target")
     # gamma = NULL: rows are used as they are
-    res = LL.ll_project(w.hidden, None, w.W_U, cfg.eps, cfg.k, w.target_ids)
+    res = project(w.hidden, None, w.W_U, cfg.eps, cfg.k, w.target_ids)
     torch.cuda.synchronize()
     got = P.to_numpy(res)
     ref = oracle_for(w, np.arange(cfg.N), gamma=None)
@@ -202,11 +213,11 @@ def test_paper_output_format_bias_and_topk_softmax():
     t = w.target_ids.cpu().numpy()
     ref = P.oracle_rows(hb, gb, wb, cfg.eps, cfg.k, t, bias=bias.cpu().numpy())
     # bias only: full-softmax probabilities
-    res = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, bias=bias)
+    res = project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, bias=bias)
     torch.cuda.synchronize()
     P.compare(P.to_numpy(res), ref, cfg.k, label="bias")
     # bias + the paper's probabilities
-    res = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, bias=bias, topk_softmax=True)
+    res = project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, bias=bias, topk_softmax=True)
     torch.cuda.synchronize()
     got = P.to_numpy(res)
     want_p = O.topk_renormalised(ref["topk_p"])
@@ -218,8 +229,8 @@ def test_paper_output_format_bias_and_topk_softmax():
     assert np.max(np.abs(got["entropy"] - ref["entropy"])) <= P.TOL_ENT      # still full-vocabulary
     assert np.max(np.abs(got["target_logp"] - ref["target_logp"])) <= P.TOL_LOGP
     # no bias, flag only, equals renormalising the plain result
-    a = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids)
-    b = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, topk_softmax=True)
+    a = project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids)
+    b = project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, topk_softmax=True)
     torch.cuda.synchronize()
     assert torch.equal(a[0], b[0])
     assert torch.allclose(b[1], a[1] / a[1].sum(1, keepdim=True), atol=1e-6)
@@ -235,23 +246,25 @@ def test_caller_workspace_and_stream():
     s = torch.cuda.Stream()
     s.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(s):
-        a = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, stream=s)
-        b = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, stream=s)
+        a = project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, stream=s)
+        b = project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, stream=s)
     s.synchronize()
     for x, y in zip(a, b):
         assert torch.equal(x, y)
     ref = oracle_for(w, np.arange(cfg.N))
     P.compare(P.to_numpy(a), ref, cfg.k, label="workspace")
     with pytest.raises(LL.LLError) as e:
-        LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws[:need - 256])
+        project(w.hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws[:need - 256])
     assert e.value.code == LL.LL_EWORKSPACE
 
 
-def test_timed_variant_matches():
+def test_timed_variant_matches(gemm_path):
+    if gemm_path != 2:
+        pytest.skip("ll_project_timed has no kernel-choice argument")
     say("ll_project_timed")
     w = WL.make_workload("tiny", DEV)
-    a = LL.ll_project(w.hidden, w.gamma, w.W_U, 1e-5, 5, w.target_ids)
-    b = LL.ll_project(w.hidden, w.gamma, w.W_U, 1e-5, 5, w.target_ids, timed=True)
+    a = project(w.hidden, w.gamma, w.W_U, 1e-5, 5, w.target_ids)
+    b = project(w.hidden, w.gamma, w.W_U, 1e-5, 5, w.target_ids, timed=True)
     torch.cuda.synchronize()
     for x, y in zip(a, b[:4]):
         assert torch.equal(x, y)
@@ -268,8 +281,6 @@ def test_full_size_config_sampled_rows(name, gemm_path):
     # norm applied inside the A-tile load, runs the first of them at full size on a smaller row sample.
     if gemm_path != 2 and name != "qwen3-4b":
         pytest.skip("the register-staged kernel runs one full-size config (qwen3-4b); the others are the default kernel's")
-    if gemm_path == 2:
-        LL.ll_set_gemm_path(0)
     cfg = WL.CONFIGS[name]
     say(f"full size {name}: N={cfg.N} d={cfg.d} V={cfg.V} k={cfg.k}, kernel path {gemm_path}")
     w = WL.make_workload(cfg, DEV)
@@ -301,14 +312,13 @@ def test_full_size_paper_output_format(gemm_path):
     k = 3 selected logits only (Sec. 3.3, the format of the paper's heatmaps), sampled rows against the oracle."""
     if gemm_path != 2:
         pytest.skip("the default kernel is the one a bias selects; the other kernel's bias path is covered at small sizes")
-    LL.ll_set_gemm_path(0)
     cfg = WL.CONFIGS["llama31-70b"]
     k = 3
     say(f"full size ll_project_ex llama31-70b: bias + top-k-only softmax, k={k}")
     w = WL.make_workload(cfg, DEV)
     g = torch.Generator(device=DEV).manual_seed(17)
     bias = torch.randn((cfg.V,), generator=g, device=DEV) * 0.5
-    res = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, k, w.target_ids, bias=bias, topk_softmax=True)
+    res = project(w.hidden, w.gamma, w.W_U, cfg.eps, k, w.target_ids, bias=bias, topk_softmax=True)
     torch.cuda.synchronize()
     got = P.to_numpy(res)
     rows = WL.sample_rows(cfg, 128)
@@ -324,7 +334,7 @@ def test_full_size_paper_output_format(gemm_path):
     assert np.max(np.abs(sub["entropy"] - ref["entropy"])) <= P.TOL_ENT         # still full-vocabulary
     assert np.max(np.abs(sub["target_logp"] - ref["target_logp"])) <= P.TOL_LOGP
     # the bias matters at this size: without it the sampled rows' entropies differ by far more than the tolerance
-    plain = LL.ll_project(w.hidden, w.gamma, w.W_U, cfg.eps, k, w.target_ids)
+    plain = project(w.hidden, w.gamma, w.W_U, cfg.eps, k, w.target_ids)
     torch.cuda.synchronize()
     assert np.max(np.abs(plain[3].cpu().numpy()[rows] - ref["entropy"])) > 10 * P.TOL_ENT
     del w
@@ -337,7 +347,6 @@ def test_full_size_paper_output_format(gemm_path):
 def test_projection_replays_from_a_hip_graph(gemm_path):
     if gemm_path != 2:
         pytest.skip("one kernel path is enough for this property")
-    LL.ll_set_gemm_path(0)
     say("graph capture")
     cfg = WL.LensConfig("graph", L=2, T=300, d=256, V=5000, k=10, n_outliers=4, outlier_scale=20.0)
     w = WL.make_workload(cfg, DEV, seed=4)
@@ -346,15 +355,15 @@ def test_projection_replays_from_a_hip_graph(gemm_path):
     out = (torch.zeros((N, cfg.k), dtype=torch.int32, device=DEV), torch.zeros((N, cfg.k), dtype=torch.float32, device=DEV),
            torch.zeros((N,), dtype=torch.float32, device=DEV), torch.zeros((N,), dtype=torch.float32, device=DEV))
     hidden = w.hidden.clone()
-    eager = [t.clone() for t in LL.ll_project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids)]
+    eager = [t.clone() for t in project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids)]
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     s = torch.cuda.Stream()
     with torch.cuda.stream(s):
-        LL.ll_project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, out=out, stream=s)   # warm-up
+        project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, out=out, stream=s)   # warm-up
         s.synchronize()
         with torch.cuda.graph(g, stream=s):
-            LL.ll_project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, out=out, stream=s)
+            project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids, workspace=ws, out=out, stream=s)
     for rep in range(3):
         for t in out:
             t.zero_()
@@ -366,7 +375,7 @@ def test_projection_replays_from_a_hip_graph(gemm_path):
             assert torch.equal(got, want), f"replay {rep} differs from the eager result"
     # new input in the captured buffer, same graph
     hidden.copy_(torch.flip(w.hidden, dims=(1,)))
-    want = [t.clone() for t in LL.ll_project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids)]
+    want = [t.clone() for t in project(hidden, w.gamma, w.W_U, cfg.eps, cfg.k, w.target_ids)]
     g.replay()
     torch.cuda.synchronize()
     for got, w_ in zip(out, want):
