@@ -36,7 +36,8 @@ namespace {
 // result as it leaves the pipe; 1 % on this kernel, 3.5 % on a bare MFMA loop); W fragments
 // alternate between two register sets of eight (four tiles x two halves):
 //   slice 0    : reads the W fragments of slice 1; sends the second half of W(g+2);
-//   slices 1, 2: read the W fragments of the next slice; send A(g+2), half each (into the slot of
+//   slices 1, 2: read the W fragments of the next slice (slice 2 has its last reads out five pairs
+//                before the wait, so that they are back when slice 3 starts); send A(g+2), half each (into the slot of
 //                A(g), whose fragments all went into registers during stage g-1);
 //   wait + barrier: all loads but the last 16 (W(g+2), A(g+2)) have landed, so stage g+1 is in
 //                LDS for everyone, and everyone holds its last fragments of W(g): that slot is free;
@@ -239,10 +240,17 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   // it goes: a row tile's two fragments are dead once its four pairs are done, and the next stage's
   // slice 0 needs them in the same order, 24 MFMAs later at the least.
   // An MFMA runs for 16 cycles, so a gap between two of them holds at most two or three other
-  // instructions.  Behind the pairs with an even number goes the LDS read of one W fragment of the
-  // next slice (into nw, from the tile at LDS offset tW), behind those with an odd number a
-  // load-to-LDS or a piece of the streams' bookkeeping (HOOK); slice 3's A fragment reads go
-  // between the two MFMAs of a pair (AIN).  The fences pin that order.
+  // instructions.  Behind a pair goes the LDS read of one W fragment of the next slice (into nw,
+  // from the tile at LDS offset tW) where RD names one, and a load-to-LDS or a piece of the streams'
+  // bookkeeping where HOOK names one; slice 3's A fragment reads go between the two MFMAs of a pair
+  // (AIN).  The fences pin that order.
+  // Which pairs read: slices 0, 1 and 3 spread their eight reads over the even pairs.  Slice 2
+  // reads ahead (LL_RD_AHEAD: the last three reads pulled forward to pairs 9, 10, 11): its
+  // fragments are the ones slice 3 needs ALL of within its first four pairs (it walks row tile by
+  // row tile), right behind the wait and the barrier, and a read sent two pairs before the wait
+  // has not come back by then; measured 0.4 to 1.9 % per launch over the spread placement.  (The
+  // same move in slice 3, whose fragments the next stage's slice 0 needs as early, measured
+  // nothing: that slice's gaps already hold the eight A fragment reads.)
 #define LL_LDS_FRAG(ptr) (*reinterpret_cast<const bf16x8*>(ptr))
   // Written as an instruction so that the 64 accumulator tiles stay in AGPRs: given the builtin,
   // the register allocator keeps some of them in VGPRs and copies them in and out around the MFMA.
@@ -254,39 +262,40 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
 #define LL_SNAKE(outer, inner) (((outer) & 1) ? 3 - (inner) : (inner))
 #define LL_T(JO, P) ((JO) ? LL_SNAKE((P) / 4, (P) % 4) : (P) / 4)
 #define LL_J(JO, P) ((JO) ? (P) / 4 : LL_SNAKE((P) / 4, (P) % 4))
-#define LL_PAIR(MF0, P, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                     \
+#define LL_RD_SPREAD(P) ((P) % 2 == 0 ? (P) / 2 : -1)
+#define LL_RD_AHEAD(P) ((P) <= 8 ? ((P) % 2 == 0 ? (P) / 2 : -1) : ((P) <= 11 ? (P) - 4 : -1))
+#define LL_PAIR(MF0, P, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                 \
   acc[4 * S + LL_T(JO, P)][LL_J(JO, P)] =                                                                            \
       MF0(fw[2 * LL_T(JO, P)], fa[0][LL_J(JO, P)], acc[4 * S + LL_T(JO, P)][LL_J(JO, P)]);                           \
   AIN(P);                                                                                                            \
   LL_SCHED_FENCE();                                                                                                  \
   acc[4 * S + LL_T(JO, P)][LL_J(JO, P)] =                                                                            \
       LL_MFMA16(fw[2 * LL_T(JO, P) + 1], fa[1][LL_J(JO, P)], acc[4 * S + LL_T(JO, P)][LL_J(JO, P)]);                 \
-  if ((P) % 2 == 0) {                                                                                                \
-    nw[(P) / 2] = LL_LDS_FRAG(smem + tW + (4 * NS + (P) / 4) * 16 * (DK * 2) + f_off[((P) / 2) & 1]);                \
+  if (RD(P) >= 0) { /* fragment q = RD(P): vocabulary tile 4 NS + q / 2, K half q % 2 */                            \
+    nw[RD(P) >= 0 ? RD(P) : 0] =                                                                                     \
+        LL_LDS_FRAG(smem + tW + (4 * NS + (RD(P) >= 0 ? RD(P) : 0) / 2) * 16 * (DK * 2) + f_off[(RD(P) >= 0 ? RD(P) : 0) & 1]); \
   }                                                                                                                  \
-  else {                                                                                                             \
-    HOOK(((P) - 1) / 2);                                                                                             \
-  }                                                                                                                  \
+  HOOK(P);                                                                                                           \
   AOUT(P);                                                                                                           \
   LL_SCHED_FENCE();
-#define LL_SLICE(MF0, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                        \
+#define LL_SLICE(MF0, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                    \
   LL_SCHED_FENCE();                                                                                                  \
-  LL_PAIR(MF0, 0, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
-  LL_PAIR(MF0, 1, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
-  LL_PAIR(MF0, 2, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
-  LL_PAIR(MF0, 3, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
-  LL_PAIR(MF0, 4, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
-  LL_PAIR(MF0, 5, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
-  LL_PAIR(MF0, 6, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
-  LL_PAIR(MF0, 7, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
-  LL_PAIR(MF0, 8, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
-  LL_PAIR(MF0, 9, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                            \
-  LL_PAIR(MF0, 10, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                           \
-  LL_PAIR(MF0, 11, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                           \
-  LL_PAIR(MF0, 12, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                           \
-  LL_PAIR(MF0, 13, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                           \
-  LL_PAIR(MF0, 14, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)                                                           \
-  LL_PAIR(MF0, 15, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK)
+  LL_PAIR(MF0, 0, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                            \
+  LL_PAIR(MF0, 1, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                            \
+  LL_PAIR(MF0, 2, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                            \
+  LL_PAIR(MF0, 3, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                            \
+  LL_PAIR(MF0, 4, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                            \
+  LL_PAIR(MF0, 5, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                            \
+  LL_PAIR(MF0, 6, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                            \
+  LL_PAIR(MF0, 7, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                            \
+  LL_PAIR(MF0, 8, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                            \
+  LL_PAIR(MF0, 9, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                            \
+  LL_PAIR(MF0, 10, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                           \
+  LL_PAIR(MF0, 11, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                           \
+  LL_PAIR(MF0, 12, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                           \
+  LL_PAIR(MF0, 13, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                           \
+  LL_PAIR(MF0, 14, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)                                                           \
+  LL_PAIR(MF0, 15, S, JO, fw, nw, tW, NS, AIN, AOUT, HOOK, RD)
 
 #define LL_A_NONE(P) (void)0
   // slice 3 (row tile P / 4 in pairs 4 j .. 4 j + 3): the K half 0 fragment of a row tile is dead
@@ -300,37 +309,38 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
     fa[1][3] = LL_LDS_FRAG(smem + nA + 3 * 16 * (DK * 2) + f_off[1]);                                  \
     nA = a_flip - nA;   /* LDS reads return in order: the tile read from just now is the wavefront's to refill */ \
   }
-#define LL_HOOK_S0(I)                                \
-  if (I == 0) set_lds_dma_base(w_lds);               \
-  if (I == 3) LL_DMA_W(4);                           \
-  if (I == 4) LL_DMA_W(5);                           \
-  if (I == 5) LL_DMA_W(6);                           \
-  if (I == 6) LL_DMA_W(7);                           \
-  if (I == 7) advance_w()
+  // (hooks: what goes behind pair P of the slice, besides a fragment read)
+#define LL_HOOK_S0(P)                                \
+  if (P == 1) set_lds_dma_base(w_lds);               \
+  if (P == 7) LL_DMA_W(4);                           \
+  if (P == 9) LL_DMA_W(5);                           \
+  if (P == 11) LL_DMA_W(6);                          \
+  if (P == 13) LL_DMA_W(7);                          \
+  if (P == 15) advance_w()
   // (the A fragments of this stage were all read in the previous stage's slice 3: the slot of A(g),
   // which A(g+2) goes into, has been the wavefront's own since then)
-#define LL_HOOK_S1(I)                                \
-  if (I == 3) set_lds_dma_base(a_lds);               \
-  if (I == 4) LL_DMA_A(0);                           \
-  if (I == 5) LL_DMA_A(1);                           \
-  if (I == 6) LL_DMA_A(2);                           \
-  if (I == 7) LL_DMA_A(3)
-#define LL_HOOK_S2(I)                                \
-  if (I == 2) LL_DMA_A(4);                           \
-  if (I == 3) LL_DMA_A(5);                           \
-  if (I == 4) LL_DMA_A(6);                           \
-  if (I == 5) LL_DMA_A(7);                           \
-  if (I == 6) advance_a()
-#define LL_HOOK_S3(I)                                \
-  if (I == 3) set_lds_dma_base(w_lds);               \
-  if (I == 4) LL_DMA_W(0);                           \
-  if (I == 5) {                                      \
+#define LL_HOOK_S1(P)                                \
+  if (P == 7) set_lds_dma_base(a_lds);               \
+  if (P == 9) LL_DMA_A(0);                           \
+  if (P == 11) LL_DMA_A(1);                          \
+  if (P == 13) LL_DMA_A(2);                          \
+  if (P == 15) LL_DMA_A(3)
+#define LL_HOOK_S2(P)   /* (pair 9 is left to the fragment reads that slice 2 pulls forward) */ \
+  if (P == 5) LL_DMA_A(4);                           \
+  if (P == 7) LL_DMA_A(5);                           \
+  if (P == 11) LL_DMA_A(6);                          \
+  if (P == 13) LL_DMA_A(7);                          \
+  if (P == 15) advance_a()
+#define LL_HOOK_S3(P)                                \
+  if (P == 7) set_lds_dma_base(w_lds);               \
+  if (P == 9) LL_DMA_W(0);                           \
+  if (P == 11) {                                     \
     LL_DMA_W(1);                                     \
     nnW = nW + SLOT_BYTES >= W_SLOTS * SLOT_BYTES ? 0 : nW + SLOT_BYTES;   \
     LL_PIN_S(nnW);                                   \
   }                                                  \
-  if (I == 6) LL_DMA_W(2);                           \
-  if (I == 7) {   /* every even pair of the slice reads a W fragment from nW: move on after the last */ \
+  if (P == 13) LL_DMA_W(2);                          \
+  if (P == 15) {   /* every even pair of the slice reads a W fragment from nW: move on after the last */ \
     LL_DMA_W(3);                                     \
     cW = nW;                                         \
     nW = nnW;                                        \
@@ -345,13 +355,13 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
     f32x4 acc[16][4];   // first written by the K half 0 MFMAs of stage 0, with C = 0
     // One stage; MF0 is the MFMA form of K half 0: from zero in a tile's first stage, accumulating after.
 #define LL_STAGE(MF0)                                                                                  \
-    LL_SLICE(MF0, 0, 1, fw0, fw1, cW, 1, LL_A_NONE, LL_A_NONE, LL_HOOK_S0)                             \
-    LL_SLICE(MF0, 1, 0, fw1, fw0, cW, 2, LL_A_NONE, LL_A_NONE, LL_HOOK_S1)                             \
-    LL_SLICE(MF0, 2, 0, fw0, fw1, cW, 3, LL_A_NONE, LL_A_NONE, LL_HOOK_S2)                             \
+    LL_SLICE(MF0, 0, 1, fw0, fw1, cW, 1, LL_A_NONE, LL_A_NONE, LL_HOOK_S0, LL_RD_SPREAD)               \
+    LL_SLICE(MF0, 1, 0, fw1, fw0, cW, 2, LL_A_NONE, LL_A_NONE, LL_HOOK_S1, LL_RD_SPREAD)               \
+    LL_SLICE(MF0, 2, 0, fw0, fw1, cW, 3, LL_A_NONE, LL_A_NONE, LL_HOOK_S2, LL_RD_AHEAD)                \
     /* stage g+1 landed (W(g+2) and A(g+2) may still be out); all my reads of W(g) are done */         \
     __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LOADS_PER_TILE, 0));                                    \
     __syncthreads();                                                                                   \
-    LL_SLICE(MF0, 3, 1, fw1, fw0, nW, 0, LL_AIN_S3, LL_AOUT_S3, LL_HOOK_S3)
+    LL_SLICE(MF0, 3, 1, fw1, fw0, nW, 0, LL_AIN_S3, LL_AOUT_S3, LL_HOOK_S3, LL_RD_SPREAD)
     LL_STAGE(LL_MFMA16_Z)
     for (int kt = 1; kt < KT; ++kt) {
       LL_STAGE(LL_MFMA16)
@@ -360,6 +370,8 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
     EPI::tile(acc, st, tile * BM, p, my_row);
   }
 #undef LL_PAIR
+#undef LL_RD_SPREAD
+#undef LL_RD_AHEAD
 #undef LL_T
 #undef LL_J
 #undef LL_SNAKE
