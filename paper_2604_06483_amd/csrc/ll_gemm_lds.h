@@ -154,7 +154,7 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   // (LL_PIN_S: the value is computed where the statement stands; without it the compiler gathers
   // the scalar updates of a whole stage into one lump, and the matrix pipe idles behind it.)
 #define LL_PIN_S(x) asm volatile("" : "+s"(x))
-  int w_tile = tile0, w_kt = 0, a_kt = 0;
+  int w_tile = tile0, w_kt = 0;
   unsigned w_lds = lds_mid, a_lds = lds_mid + W_SLOTS * SLOT_BYTES;   // M0 value of the stream's next tile
   const unsigned char* w_base = w_tile_base(tile0);
   const unsigned char* a_base = a_base0;
@@ -173,13 +173,11 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
     LL_PIN_S(w_lds);
     LL_PIN_S(w_base);
   };
-  auto advance_a = [&]() {
+  const unsigned char* const a_end = a_base0 + (int64_t)KT * (DK * 2);   // one past the panel's last K stage
+  auto advance_a = [&]() {   // (a handful of scalar instructions: a long run of them between two MFMAs idles the matrix pipe)
     a_lds = a_lds_flip - a_lds;
     a_base += DK * 2;
-    if (++a_kt == KT) {
-      a_kt = 0;
-      a_base = a_base0;
-    }
+    if (a_base == a_end) a_base = a_base0;
     LL_PIN_S(a_lds);
     LL_PIN_S(a_base);
   };
@@ -329,9 +327,9 @@ void ll_lens_gemm_dma_kernel(const GemmArgs p) {
   if (P == 5) LL_DMA_A(4);                           \
   if (P == 7) LL_DMA_A(5);                           \
   if (P == 11) LL_DMA_A(6);                          \
-  if (P == 13) LL_DMA_A(7);                          \
-  if (P == 15) advance_a()
-#define LL_HOOK_S3(P)                                \
+  if (P == 13) LL_DMA_A(7)
+#define LL_HOOK_S3(P)   /* (the A stream moves on here, behind the barrier, not in the last gap before the wait) */ \
+  if (P == 1) advance_a();                           \
   if (P == 7) set_lds_dma_base(w_lds);               \
   if (P == 9) LL_DMA_W(0);                           \
   if (P == 11) {                                     \
