@@ -105,9 +105,10 @@ int ll_project_ex(const ll_shape* shape, void* workspace, size_t workspace_bytes
 /*
  * ll_project with per-phase timing, for benchmarks.  Same arguments and results; in addition
  * phase_ms (HOST pointer, 3 floats) receives the GPU time in milliseconds, summed over the row
- * passes, of {RMS statistics, fused projection kernel, split merge}, measured with HIP events
- * on `stream`.  Unlike ll_project this call creates events and SYNCHRONISES the stream before
- * it returns.
+ * passes, of {normalised panel (RMS statistics where the register-staged kernel runs), fused
+ * projection kernel, split merge}, measured with HIP events recorded on `stream` around every
+ * launch.  Unlike ll_project this call SYNCHRONISES the stream before it returns; the events
+ * are created by a thread's first timed call and kept for its later ones.
  */
 int ll_project_timed(const ll_shape* shape, void* workspace, size_t workspace_bytes,
                      const void* hidden, const void* gamma, const void* W_U,
@@ -132,7 +133,9 @@ int ll_project_timed(const ll_shape* shape, void* workspace, size_t workspace_by
  *
  * All calls on one GPU share that GPU's buffer: two calls whose kernels may overlap on the same
  * GPU (different streams, different threads) race; calls queued on one stream are safe.  The
- * buffer keeps the last call's contents and nothing in it needs clearing.  The first call on a
+ * buffer keeps the last call's contents; the one part that has to start at zero (the top-k bounds
+ * the vocabulary splits share) is cleared by a small fill kernel at the start of every call, as
+ * in ll_project, never by a memset (the call stays capturable).  The first call on a
  * device looks up the buffer's address (no allocation) and sets a kernel attribute: make it
  * outside stream capture.
  */

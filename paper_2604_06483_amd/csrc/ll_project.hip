@@ -776,9 +776,10 @@ int sweep_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes, c
 // Allocation-free variant: the workspace of ll_project in a device array of this library, for
 // callers that cannot allocate.  The array's name is a host-side handle, not a device address:
 // its address on the current device is looked up once per device and only that pointer is used
-// from then on.  Nothing in the workspace has to start at zero (inv_rms, the partials and the
-// panel are each written in full before they are read), so stale contents of an earlier call do
-// not matter.
+// from then on.  inv_rms, the partials and the panel are each written in full before they are
+// read; the shared top-k bounds, which have to start at zero, are cleared by a fill kernel at the
+// start of every call (project_impl does that for any workspace): stale contents of an earlier
+// call do not matter.
 // ---------------------------------------------------------------------------------------
 static __device__ __align__(256) unsigned char ll_static_scratch[LL_STATIC_SCRATCH_BYTES];
 constexpr int MAX_DEVICES = 64;
