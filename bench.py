@@ -309,6 +309,17 @@ def aux_figures(result, args, cfg, w, LL, torch, timed_ms, ws, sws, v, steered, 
     except torch.OutOfMemoryError:                      # a smaller card: the figure is skipped, nothing else depends on it
         result["capture_three_types"] = None
 
+    # The lens of one decoding step (the newest token's row of every layer) through the entry point that allocates
+    # nothing: so few rows make the call a single read of W_U, cut into one vocabulary split per compute unit.
+    step_rows = w.hidden[:, -1].contiguous()
+    step_tgt = w.target_ids.reshape(cfg.L, cfg.T)[:, -1].contiguous()
+    step_out = LL.ll_project_static(step_rows, w.gamma, w.W_U, cfg.eps, k, step_tgt, stream=stream)
+    t_step = timed_ms(lambda: LL.ll_project_static(step_rows, w.gamma, w.W_U, cfg.eps, k, step_tgt, out=step_out, stream=stream),
+                      reps=20)
+    result["decode_step_lens"] = {"rows": cfg.L, "ll_project_static_us": t_step * 1e3,
+                                  "W_U_read_GBs": 2.0 * V * d / (t_step * 1e-3) / 1e9, "hbm_peak_GBs": PEAK_HBM_GBS}
+    del step_rows, step_tgt, step_out
+
     # Dose-response sweep: the middle layer's rows read out for nine alphas, once as one ll_steer_sweep pass over W_U
     # and once as nine ll_steer_inject + ll_project(gamma=None, k=1) pairs.
     if d <= 40960:

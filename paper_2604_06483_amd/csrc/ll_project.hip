@@ -195,10 +195,16 @@ __device__ __forceinline__ int group_min_int(int x, int width) {
   return x;
 }
 
-// One wavefront per row, lane s = split s (splits <= 64).  The row's lists (splits x k pairs, contiguous in the
-// workspace) are first copied into LDS with coalesced loads: the k steps of the merge are a chain, each needing the
-// next entry of whichever list won the step before, and from LDS that costs a fraction of a trip to memory.
-// Dynamic LDS: 4 wavefronts x splits x k x 8 bytes (at most 64 KB).
+// One wavefront per row; lane s holds the lists of splits [s LPL, s LPL + LPL) (LPL = 1 while the splits fit one
+// lane each; 4 when a pass of few rows cuts the vocabulary finer than that so as to fill the chip).  The row's
+// lists (splits x k pairs, contiguous in the workspace) are first copied into LDS with coalesced loads: the k steps
+// of the merge are a chain, each needing the next entry of whichever list won the step before, and from LDS that
+// costs a fraction of a trip to memory.
+// Dynamic LDS: wavefronts of the block x splits x k x 8 bytes (at most 64 KB: four wavefronts at LPL = 1, one at 4).
+constexpr int MERGE_LPL = 4;                              // lists per lane of the merge when splits > 64
+constexpr int MAX_PROJECT_SPLITS = MAX_SPLITS * MERGE_LPL;   // vocabulary splits per row block of the projection
+
+template <int LPL>
 __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict__ stats, const uint2* __restrict__ top,
                                                        int rows, int splits, int k, int V, int topk_softmax,
                                                        const int32_t* __restrict__ target, int32_t* __restrict__ out_ids,
@@ -217,14 +223,28 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict_
   }
   __syncthreads();
   if (!valid) return;
-  const bool live = lane < splits;
-  float4 q = make_float4(-INFINITY, 0.f, 0.f, -INFINITY);
-  if (live) q = stats[(int64_t)row * splits + lane];
-  const float M = wave_max(q.x);
-  const float sc = live ? __builtin_amdgcn_exp2f((q.x - M) * LOG2E) : 0.f;
-  const float S = wave_sum(sc * q.y);
-  const float T = wave_sum(sc * q.z);
-  const float zt = wave_max(q.w);
+  bool live[LPL];
+  float4 q[LPL];
+  float m_lane = -INFINITY, zt_lane = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < LPL; ++i) {
+    live[i] = lane * LPL + i < splits;
+    q[i] = make_float4(-INFINITY, 0.f, 0.f, -INFINITY);
+    if (live[i]) q[i] = stats[(int64_t)row * splits + lane * LPL + i];
+    m_lane = fmaxf(m_lane, q[i].x);
+    zt_lane = fmaxf(zt_lane, q[i].w);
+  }
+  const float M = wave_max(m_lane);
+  float s_lane = 0.f, t_lane = 0.f;
+#pragma unroll
+  for (int i = 0; i < LPL; ++i) {
+    const float sc = live[i] ? __builtin_amdgcn_exp2f((q[i].x - M) * LOG2E) : 0.f;
+    s_lane += sc * q[i].y;
+    t_lane += sc * q[i].z;
+  }
+  const float S = wave_sum(s_lane);
+  const float T = wave_sum(t_lane);
+  const float zt = wave_max(zt_lane);
   const float logS = logf(S);
   if (lane == 0) {
     if (bound != nullptr) bound[row] = 0u;   // the projection kernel of this pass is done with it: clear it for the next pass
@@ -235,33 +255,50 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict_
     }
   }
   // k-way merge of the per-split sorted lists (descending logit, ascending id): every lane holds the
-  // head of its list; the wavefront's best head goes out and that lane moves on.
-  const uint2* tl = mine + (live ? lane : 0) * k;
-  int head = 0;
-  float z = -INFINITY;
-  int id = INT_MAX;
-  if (live) {
-    const uint2 e = tl[0];
-    z = __uint_as_float(e.x);
-    id = (int)e.y;
+  // heads of its lists; the wavefront's best head goes out and that list moves on.
+  const uint2* tl = mine + lane * LPL * k;
+  int head[LPL];
+  float z[LPL];
+  int id[LPL];
+#pragma unroll
+  for (int i = 0; i < LPL; ++i) {
+    head[i] = 0;
+    z[i] = -INFINITY;
+    id[i] = INT_MAX;
+    if (live[i]) {
+      const uint2 e = tl[i * k];
+      z[i] = __uint_as_float(e.x);
+      id[i] = (int)e.y;
+    }
   }
   float z0 = 0.f, sk = 0.f;   // top-k-only softmax: the largest selected logit and the sum over the selection
   float my_z = 0.f;           // lane j keeps the j-th selected logit and id, written out together at the end
   int my_id = 0;
-  int width = 1;   // lanes that hold a list, rounded up to a power of two (lanes past `splits` hold the neutral head)
-  while (width < splits) width <<= 1;
+  int width = 1;   // lanes that hold a list, rounded up to a power of two (lanes past them hold the neutral head)
+  while (width * LPL < splits) width <<= 1;
   for (int j = 0; j < k; ++j) {
-    const float bz = group_max(z, width);
-    const int bi = group_min_int(z == bz ? id : INT_MAX, width);
-    if (live && z == bz && id == bi) {   // ids are distinct: exactly one lane
-      ++head;
-      if (head < k) {
-        const uint2 e = tl[head];
-        z = __uint_as_float(e.x);
-        id = (int)e.y;
-      } else {
-        z = -INFINITY;
-        id = INT_MAX;
+    float lz = z[0];   // this lane's best head: largest logit, smallest id among equals
+    int li = id[0];
+#pragma unroll
+    for (int i = 1; i < LPL; ++i) {
+      const bool better = z[i] > lz || (z[i] == lz && id[i] < li);
+      lz = better ? z[i] : lz;
+      li = better ? id[i] : li;
+    }
+    const float bz = group_max(lz, width);
+    const int bi = group_min_int(lz == bz ? li : INT_MAX, width);
+#pragma unroll
+    for (int i = 0; i < LPL; ++i) {
+      if (live[i] && z[i] == bz && id[i] == bi) {   // ids are distinct: exactly one list of one lane
+        ++head[i];
+        if (head[i] < k) {
+          const uint2 e = tl[i * k + head[i]];
+          z[i] = __uint_as_float(e.x);
+          id[i] = (int)e.y;
+        } else {
+          z[i] = -INFINITY;
+          id[i] = INT_MAX;
+        }
       }
     }
     // (lanes past `width` did not take part: what they keep comes from lane 0)
@@ -416,7 +453,7 @@ Plan make_plan(const ll_shape* s, int k, int chunk_rows = CHUNK_ROWS) {
   off = align_up(off + (size_t)((s->V + BM - 1) / BM) * BM * sizeof(float), 256);
   const size_t rows = (size_t)(s->N < chunk_rows ? s->N : chunk_rows);
   p.off_stats = off;
-  const size_t partials = rows * MAX_SPLITS < (size_t)MAX_PARTIALS ? rows * MAX_SPLITS : (size_t)MAX_PARTIALS;
+  const size_t partials = rows * MAX_PROJECT_SPLITS < (size_t)MAX_PARTIALS ? rows * MAX_PROJECT_SPLITS : (size_t)MAX_PARTIALS;
   off = align_up(off + partials * sizeof(float4), 256);
   p.off_top = off;
   off = align_up(off + partials * (size_t)k * sizeof(uint2), 256);
@@ -555,8 +592,10 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
       LL_CHECK_F(hipGetLastError());
     }
     const int row_blocks = (rows + BN - 1) / BN;
+    // One workgroup per compute unit: a pass of few rows cuts the vocabulary finer (its cost is then the one read
+    // of W_U, spread over every compute unit's share of the memory system).
     int splits = NUM_CU / row_blocks;
-    if (splits > MAX_SPLITS) splits = MAX_SPLITS;
+    if (splits > MAX_PROJECT_SPLITS) splits = MAX_PROJECT_SPLITS;
     if (splits > tiles) splits = tiles;
     if (splits < 1) splits = 1;
     GemmArgs a;
@@ -582,11 +621,18 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHREADS), lds, stream, a);
     LL_CHECK_F(hipGetLastError());
     LL_CHECK_F(mark());
-    hipLaunchKernelGGL(ll_merge_kernel, dim3((rows + 3) / 4), dim3(256), (size_t)4 * splits * k * sizeof(uint2), stream,
-                       (const float4*)stats, (const uint2*)top,
-                       rows, splits, k, V, (flags & LL_FLAG_TOPK_SOFTMAX) ? 1 : 0, a.target, out_topk_ids + r0 * k,
-                       out_topk_p + r0 * k,
-                       out_target_logp ? out_target_logp + r0 : nullptr, out_entropy + r0, bound);
+    if (splits <= MAX_SPLITS)
+      hipLaunchKernelGGL(ll_merge_kernel<1>, dim3((rows + 3) / 4), dim3(256), (size_t)4 * splits * k * sizeof(uint2), stream,
+                         (const float4*)stats, (const uint2*)top,
+                         rows, splits, k, V, (flags & LL_FLAG_TOPK_SOFTMAX) ? 1 : 0, a.target, out_topk_ids + r0 * k,
+                         out_topk_p + r0 * k,
+                         out_target_logp ? out_target_logp + r0 : nullptr, out_entropy + r0, bound);
+    else   // (only passes of at most three row blocks get here: one wavefront per block keeps the lists within 64 KB of LDS)
+      hipLaunchKernelGGL(ll_merge_kernel<MERGE_LPL>, dim3(rows), dim3(64), (size_t)splits * k * sizeof(uint2), stream,
+                         (const float4*)stats, (const uint2*)top,
+                         rows, splits, k, V, (flags & LL_FLAG_TOPK_SOFTMAX) ? 1 : 0, a.target, out_topk_ids + r0 * k,
+                         out_topk_p + r0 * k,
+                         out_target_logp ? out_target_logp + r0 : nullptr, out_entropy + r0, bound);
     LL_CHECK_F(hipGetLastError());
     LL_CHECK_F(mark());
   }

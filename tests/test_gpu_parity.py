@@ -79,7 +79,11 @@ RAGGED = [
     ("lds-ragged",     3, 171,  256, 3333, 12, 2),      # N=513: 3 row blocks, the last with one row; 14 tiles, last partial
     ("lds-k32",        2, 150,  320, 5000, 32, 0),      # 5 K stages, longest top-k list
     ("lds-one-stage",  1, 300,   64, 1500,  5, 0),      # a single K stage per tile
-    ("lds-64-splits",  1,  64,  128, 20000, 20, 0),     # one row block: 64 vocabulary splits of one or two tiles
+    ("lds-79-splits",  1,  64,  128, 20000, 20, 0),     # one row block: one vocabulary split per tile, four lists per merging lane
+    ("lds-256-splits", 1,  81,  128, 70000, 20, 2),     # a decoding step's rows: 274 tiles over 256 splits
+    ("lds-256-k32",    1,  40,   64, 70000, 32, 0),     # the same with the longest lists: 64 KB of them per row in the merge
+    ("lds-128-splits", 2, 200,  192, 40000, 10, 2),     # two row blocks (the second ragged): 128 splits each
+    ("lds-85-splits",  3, 250,   64, 30000,  4, 0),     # three row blocks: 85 splits, the last merging lane with one list
     ("lds-long-k",     1, 300, 16384, 1000, 10, 4),     # twice the largest paper-shaped hidden size: 256 K stages per tile
 ]
 
