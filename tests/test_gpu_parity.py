@@ -101,6 +101,38 @@ def test_ragged_shapes_all_rows(case):
     say(f"{name}: {rep}")
 
 
+def random_shapes(n, seed):
+    """Seeded shapes over the whole ragged range: both kernels' d classes, one to three row blocks (every
+    split count from 1 to 256), k from 1 to the maximum."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        d = int(rng.choice([8 * int(rng.integers(1, 130)), 64 * int(rng.integers(1, 17))]))
+        N = int(rng.choice([int(rng.integers(1, 64)), int(rng.integers(64, 257)), int(rng.integers(257, 700))]))
+        V = int(rng.choice([int(rng.integers(33, 600)), int(rng.integers(600, 9000)), int(rng.integers(9000, 70000))]))
+        k = int(rng.choice([1, int(rng.integers(2, 13)), int(rng.integers(13, 33))]))
+        if N * V * d > 6e9:          # keep the oracle's contraction to a few seconds per case
+            V = max(33, int(6e9 / (N * d)))
+        out.append((f"r{i}", N, d, V, min(k, V), int(rng.integers(0, 3))))
+    return out
+
+
+RANDOM = random_shapes(16, seed=20260406)
+
+
+@pytest.mark.parametrize("case", RANDOM, ids=[f"{c[0]}-N{c[1]}-d{c[2]}-V{c[3]}-k{c[4]}" for c in RANDOM])
+def test_random_shapes_all_rows(case):
+    name, N, d, V, k, n_out = case
+    say(f"random {name}: N={N} d={d} V={V} k={k} outliers={n_out}")
+    cfg = WL.LensConfig(name, L=1, T=N, d=d, V=V, k=k, n_outliers=min(n_out, d), outlier_scale=20.0)
+    w = WL.make_workload(cfg, DEV, seed=11)
+    got = run_project(w)
+    ref = oracle_for(w, np.arange(cfg.N))
+    rep = P.compare(got, ref, k, label=name)
+    P.check_invariants(got, V, k, label=name)
+    say(f"{name}: {rep}")
+
+
 def test_large_logit_scale():
     """W_U with std 0.3: logits of tens of nats, sharply peaked rows, entropy near zero for some."""
     say("large logit scale")
