@@ -71,3 +71,42 @@ def test_oversized_shape_is_refused():
     with pytest.raises(LL.LLError) as e:
         LL.ll_project_static(h, None, w, 1e-5, 3)
     assert e.value.code == LL.LL_ESCRATCH
+
+
+def test_replays_from_a_hip_graph_between_other_calls():
+    """The callers this entry point is for: one decoding step's rows, captured once and replayed, with other calls
+    on the same static buffer (a different shape, several passes) between the replays.  Every replay gives the
+    eager call's bits."""
+    step = WL.LensConfig("static-graph", L=81, T=1, d=1024, V=70000, k=20, n_outliers=4, outlier_scale=20.0)
+    other = WL.LensConfig("static-between", L=2, T=300, d=8192, V=1500, k=20)
+    say(f"ll_project_static under graph capture: N={step.N} d={step.d} V={step.V} k={step.k}")
+    w = WL.make_workload(step, DEV, seed=16)
+    wo = WL.make_workload(other, DEV, seed=17)
+    N, k = step.N, step.k
+    hidden = w.hidden.clone()
+    out = (torch.zeros((N, k), dtype=torch.int32, device=DEV), torch.zeros((N, k), dtype=torch.float32, device=DEV),
+           torch.zeros((N,), dtype=torch.float32, device=DEV), torch.zeros((N,), dtype=torch.float32, device=DEV))
+    eager = [t.clone() for t in LL.ll_project(hidden, w.gamma, w.W_U, step.eps, k, w.target_ids)]
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        LL.ll_project_static(hidden, w.gamma, w.W_U, step.eps, k, w.target_ids, out=out, stream=s)   # first use: set-up
+        s.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            LL.ll_project_static(hidden, w.gamma, w.W_U, step.eps, k, w.target_ids, out=out, stream=s)
+    for rep in range(3):
+        for t in out:
+            t.zero_()
+        LL.ll_project_static(wo.hidden, wo.gamma, wo.W_U, other.eps, other.k, wo.target_ids)   # scribbles on the buffer
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for name, got, want in zip(("ids", "p", "logp", "entropy"), out, eager):
+            assert torch.equal(got, want), f"replay {rep}: {name} differs from the eager ll_project"
+    hidden.copy_(torch.flip(w.hidden, dims=(0,)))                   # new rows in the captured buffer, same graph
+    want = [t.clone() for t in LL.ll_project(hidden, w.gamma, w.W_U, step.eps, k, w.target_ids)]
+    g.replay()
+    torch.cuda.synchronize()
+    for got, w_ in zip(out, want):
+        assert torch.equal(got, w_)
