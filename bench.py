@@ -335,7 +335,7 @@ def aux_figures(result, args, cfg, w, LL, torch, timed_ms, ws, sws, v, steered, 
                 LL.ll_project(steered, None, w.W_U, cfg.eps, 1, tgt_layer, workspace=ws, stream=stream)
         t_pairs = timed_ms(nine_pairs)
         del sww
-        # with the three most likely tokens per alpha (the paper's figures): lists of four alphas per pass over W_U
+        # with the three most likely tokens per alpha (the paper's figures): lists for five alphas per pass over W_U
         sww3 = torch.empty(LL.ll_steer_sweep_workspace_bytes(cfg.T, d, V, len(alphas), 3), dtype=torch.uint8, device=dev)
         t_sweep3 = timed_ms(lambda: LL.ll_steer_sweep(layer, w.gamma, w.W_U, cfg.eps, v, alphas, tgt_layer, k=3, workspace=sww3,
                                                       stream=stream))

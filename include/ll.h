@@ -251,9 +251,9 @@ int ll_capture_append(const ll_capture_shape* shape, void* store, const void* sl
  * ll_steer_sweep_topk: the same with the k most likely tokens per alpha and row instead of one
  * (1 <= k <= LL_SWEEP_KMAX; the paper's figures list k = 3), sorted as in ll_project:
  *   out_topk_ids [n_alpha, N, k] int32,  out_topk_p [n_alpha, N, k] fp32 (full-softmax probabilities)
- * With k == 1 it is ll_steer_sweep.  With k > 1 the lists of four alphas are what fits the
- * register file beside the accumulators, so the call makes ceil(n_alpha / 4) passes over W_U
- * (nine alphas: three passes, against nine for ll_steer_inject + ll_project pairs).  Workspace:
+ * With k == 1 it is ll_steer_sweep.  With k > 1 the lists of five alphas are what fits the
+ * register file beside the accumulators, so the call makes ceil(n_alpha / 5) passes over W_U
+ * (nine alphas: two passes, against nine for ll_steer_inject + ll_project pairs).  Workspace:
  * ll_steer_sweep_topk_workspace_bytes(shape, n_alpha, k).
  */
 #define LL_SWEEP_MAX 9

@@ -5,6 +5,7 @@
 // Follows the paper's Sec. 3.3 (Eq. 1 and "Top-k extraction") and Alg. 1 Phase 2; the logits of
 // Eq. 1 live only in MFMA accumulators.
 #include "ll_epilogue.h"
+#include "ll_epilogue_sweep.h"
 #include "ll_gemm_lds.h"
 #include "ll_gemm_staged.h"
 

@@ -98,7 +98,7 @@ def test_sweep_matches_oracle(N, d, V, n_alpha, gamma):
 
 
 @pytest.mark.parametrize("N,d,V,n_alpha,k,gamma", [
-    (300, 512, 5000, 9, 3, True),     # nine alphas, three passes of the kernel (4 + 4 + 1), two row blocks
+    (300, 512, 5000, 9, 3, True),     # nine alphas, two passes of the kernel (5 + 4), two row blocks
     (257, 128, 777, 5, 4, True),      # the longest list, ragged vocabulary
     (64, 256, 4096, 4, 2, False),     # one pass; rows already normalised
     (200, 328, 1000, 9, 3, True),     # d not a multiple of 64: the register-staged kernel
