@@ -26,38 +26,35 @@ __device__ __forceinline__ void sweep_group(const ACC& acc, SweepState& st, int 
                                             const GemmArgs& p) {
   const int g0 = v0 + 32 * I;
   const int tl = st.tgt - g0;
+  // The group's unshifted logits, fetched from the accumulators once; every alpha adds its table
+  // entries on the fly, twice (for the maximum, then for the sums): an add costs a quarter of the
+  // accumulator read and lane transpose it replaces, and a second array of 32 would not fit.
+  float x[32];
+  load_group<I>(acc, x);
   if (__builtin_amdgcn_ballot_w64((unsigned)tl < 32u) != 0) {
-    float x[32];
-    load_group<I>(acc, x);
 #pragma unroll
     for (int o = 0; o < 32; ++o)
       if (tl == o) st.z_tgt = x[o];
   }
+  if (partial) {   // only the last tile of the vocabulary: a real branch (the empty asm keeps it one)
+    asm volatile("");
+#pragma unroll
+    for (int o = 0; o < 32; ++o)
+      if (g0 + o >= V) x[o] = NEG_BIG;   // (the table is zero there, and no alpha u comes near this magnitude)
+  }
 #pragma unroll
   for (int a = 0; a < SWEEP_MAX; ++a) {
     if (a < p.n_alpha) {
-      // The group's logits are fetched from the accumulators again for every alpha: keeping
-      // them next to the shifted copy would not fit the register file.
       const_f32_ptr au = (const_f32_ptr)(uintptr_t)(p.au + (int64_t)a * p.au_stride + g0);
-      float y[32];
-      load_group<I>(acc, y);
+      float gmax = x[0] + au[0];
 #pragma unroll
-      for (int o = 0; o < 32; ++o) y[o] += au[o];
-      if (partial) {   // only the last tile of the vocabulary: a real branch (the empty asm keeps it one)
-        asm volatile("");
-#pragma unroll
-        for (int o = 0; o < 32; ++o)
-          if (g0 + o >= V) y[o] = NEG_BIG;
-      }
-      float gmax = y[0];
-#pragma unroll
-      for (int o = 1; o < 32; ++o) gmax = fmaxf(gmax, y[o]);
+      for (int o = 1; o < 32; ++o) gmax = fmaxf(gmax, x[o] + au[o]);
       if (gmax > st.m[a]) {
         // a new maximum for this lane: ids come in increasing order, so strictly greater is the
         // tie rule, and within the group the lowest position with that value wins
         int pos = 0;
 #pragma unroll
-        for (int o = 31; o >= 0; --o) pos = (y[o] == gmax) ? o : pos;
+        for (int o = 31; o >= 0; --o) pos = (x[o] + au[o] == gmax) ? o : pos;
         const float sc = __builtin_amdgcn_exp2f((st.m[a] - gmax) * LOG2E);   // first group: exp2(-inf) = 0
         st.s[a] *= sc;
         st.t[a] *= sc;
@@ -68,9 +65,10 @@ __device__ __forceinline__ void sweep_group(const ACC& acc, SweepState& st, int 
       float s4[4] = {0.f, 0.f, 0.f, 0.f}, t4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int o = 0; o < 32; ++o) {
-        const float e = __builtin_amdgcn_exp2f(fmaf(y[o], LOG2E, -mb));
+        const float y = x[o] + au[o];
+        const float e = __builtin_amdgcn_exp2f(fmaf(y, LOG2E, -mb));
         s4[o & 3] += e;
-        t4[o & 3] = fmaf(e, y[o], t4[o & 3]);
+        t4[o & 3] = fmaf(e, y, t4[o & 3]);
       }
       st.s[a] += (s4[0] + s4[1]) + (s4[2] + s4[3]);
       st.t[a] += (t4[0] + t4[1]) + (t4[2] + t4[3]);
@@ -161,30 +159,26 @@ __device__ __forceinline__ void sweep_topk_group(const ACC& acc, SweepTopKState&
                                                  const GemmArgs& p) {
   const int g0 = v0 + 32 * I;
   const int tl = st.tgt - g0;
+  float x[32];   // the group's unshifted logits, fetched once (see sweep_group)
+  load_group<I>(acc, x);
   if (__builtin_amdgcn_ballot_w64((unsigned)tl < 32u) != 0) {
-    float x[32];
-    load_group<I>(acc, x);
 #pragma unroll
     for (int o = 0; o < 32; ++o)
       if (tl == o) st.z_tgt = x[o];
+  }
+  if (partial) {   // only the last tile of the vocabulary: a real branch (the empty asm keeps it one)
+    asm volatile("");
+#pragma unroll
+    for (int o = 0; o < 32; ++o)
+      if (g0 + o >= V) x[o] = NEG_BIG;
   }
 #pragma unroll
   for (int a = 0; a < SWEEP_TOPK_ALPHAS; ++a) {
     if (a < p.n_alpha) {
       const_f32_ptr au = (const_f32_ptr)(uintptr_t)(p.au + (int64_t)a * p.au_stride + g0);
-      float y[32];
-      load_group<I>(acc, y);
+      float gmax = x[0] + au[0];
 #pragma unroll
-      for (int o = 0; o < 32; ++o) y[o] += au[o];
-      if (partial) {   // only the last tile of the vocabulary: a real branch (the empty asm keeps it one)
-        asm volatile("");
-#pragma unroll
-        for (int o = 0; o < 32; ++o)
-          if (g0 + o >= V) y[o] = NEG_BIG;
-      }
-      float gmax = y[0];
-#pragma unroll
-      for (int o = 1; o < 32; ++o) gmax = fmaxf(gmax, y[o]);
+      for (int o = 1; o < 32; ++o) gmax = fmaxf(gmax, x[o] + au[o]);
       if (gmax > st.m[a]) {
         const float sc = __builtin_amdgcn_exp2f((st.m[a] - gmax) * LOG2E);   // first group: exp2(-inf) = 0
         st.s[a] *= sc;
@@ -195,13 +189,17 @@ __device__ __forceinline__ void sweep_topk_group(const ACC& acc, SweepTopKState&
       float s4[4] = {0.f, 0.f, 0.f, 0.f}, t4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int o = 0; o < 32; ++o) {
-        const float e = __builtin_amdgcn_exp2f(fmaf(y[o], LOG2E, -mb));
+        const float y = x[o] + au[o];
+        const float e = __builtin_amdgcn_exp2f(fmaf(y, LOG2E, -mb));
         s4[o & 3] += e;
-        t4[o & 3] = fmaf(e, y[o], t4[o & 3]);
+        t4[o & 3] = fmaf(e, y, t4[o & 3]);
       }
       st.s[a] += (s4[0] + s4[1]) + (s4[2] + s4[3]);
       st.t[a] += (t4[0] + t4[1]) + (t4[2] + t4[3]);
       if (gmax > st.lv[a][SWEEP_KS - 1]) {
+        float y[32];   // the shifted copy exists only here, for the lanes that have a candidate
+#pragma unroll
+        for (int o = 0; o < 32; ++o) y[o] = x[o] + au[o];
         unsigned mask = candidate_mask(y, st.lv[a][SWEEP_KS - 1]);
         if (partial) mask &= (g0 + 32 <= V) ? 0xffffffffu : (g0 >= V ? 0u : (1u << (V - g0)) - 1u);
         while (mask != 0) {
