@@ -200,8 +200,10 @@ __device__ __forceinline__ int group_min_int(int x, int width) {
 // lane each; 4 when a pass of few rows cuts the vocabulary finer than that so as to fill the chip).  The row's
 // lists (splits x k pairs, contiguous in the workspace) are first copied into LDS with coalesced loads: the k steps
 // of the merge are a chain, each needing the next entry of whichever list won the step before, and from LDS that
-// costs a fraction of a trip to memory.
-// Dynamic LDS: wavefronts of the block x splits x k x 8 bytes (at most 64 KB: four wavefronts at LPL = 1, one at 4).
+// costs a fraction of a trip to memory.  At LPL = 1 a block is four wavefronts with a row each; at LPL = 4 a block
+// has ONE row, all four wavefronts copy its lists (up to 64 KB: one wavefront alone would spend its time waiting for
+// its own loads) and the first one merges.
+// Dynamic LDS: rows of the block x splits x k x 8 bytes (at most 64 KB).
 constexpr int MERGE_LPL = 4;                              // lists per lane of the merge when splits > 64
 constexpr int MAX_PROJECT_SPLITS = MAX_SPLITS * MERGE_LPL;   // vocabulary splits per row block of the projection
 
@@ -214,16 +216,19 @@ __global__ __launch_bounds__(256) void ll_merge_kernel(const float4* __restrict_
   extern __shared__ __align__(8) uint2 lists[];
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * (blockDim.x >> 6) + wave;
+  const int row = LPL == 1 ? blockIdx.x * (blockDim.x >> 6) + wave : blockIdx.x;
   const bool valid = row < rows;          // (no early return: every wavefront reaches the barrier)
   const int n_entries = splits * k;
-  uint2* mine = lists + wave * n_entries;
+  uint2* mine = LPL == 1 ? lists + wave * n_entries : lists;
   if (valid) {
     const uint2* src = top + (int64_t)row * n_entries;
-    for (int i = lane; i < n_entries; i += 64) mine[i] = src[i];
+    if (LPL == 1)
+      for (int i = lane; i < n_entries; i += 64) mine[i] = src[i];
+    else
+      for (int i = threadIdx.x; i < n_entries; i += blockDim.x) mine[i] = src[i];
   }
   __syncthreads();
-  if (!valid) return;
+  if (!valid || (LPL != 1 && wave != 0)) return;
   bool live[LPL];
   float4 q[LPL];
   float m_lane = -INFINITY, zt_lane = -INFINITY;
@@ -628,8 +633,8 @@ int project_impl(const ll_shape* shape, void* workspace, size_t workspace_bytes,
                          rows, splits, k, V, (flags & LL_FLAG_TOPK_SOFTMAX) ? 1 : 0, a.target, out_topk_ids + r0 * k,
                          out_topk_p + r0 * k,
                          out_target_logp ? out_target_logp + r0 : nullptr, out_entropy + r0, bound);
-    else   // (only passes of at most three row blocks get here: one wavefront per block keeps the lists within 64 KB of LDS)
-      hipLaunchKernelGGL(ll_merge_kernel<MERGE_LPL>, dim3(rows), dim3(64), (size_t)splits * k * sizeof(uint2), stream,
+    else   // (only passes of at most three row blocks get here: one row per block keeps the lists within 64 KB of LDS)
+      hipLaunchKernelGGL(ll_merge_kernel<MERGE_LPL>, dim3(rows), dim3(256), (size_t)splits * k * sizeof(uint2), stream,
                          (const float4*)stats, (const uint2*)top,
                          rows, splits, k, V, (flags & LL_FLAG_TOPK_SOFTMAX) ? 1 : 0, a.target, out_topk_ids + r0 * k,
                          out_topk_p + r0 * k,
