@@ -113,11 +113,14 @@ __global__ __launch_bounds__(256) void ll_fill_f32_kernel(float* __restrict__ p,
 // ---------------------------------------------------------------------------------------
 // Steering sweep, step 1: u = W_U v (one pass over W_U, HBM-bound: 2 V d bytes), written as the
 // table au[a, id] = alpha_a * u[id] that the sweep epilogue adds to the logits.  One wavefront
-// takes four vocabulary rows at a time so that a chunk of v read from LDS serves four products.
+// takes eight vocabulary rows at a time: a chunk of v read from LDS serves eight products, and
+// eight 16-byte loads per lane are in flight.
 // ---------------------------------------------------------------------------------------
 struct AlphaList {
   float a[SWEEP_MAX];
 };
+
+constexpr int UD_ROWS = 8;   // vocabulary rows a wavefront takes at a time
 
 __global__ __launch_bounds__(256) void ll_unembed_direction_kernel(const uint16_t* __restrict__ W, const float* __restrict__ v,
                                                                    int V, int d, AlphaList alphas, int n_alpha,
@@ -128,31 +131,36 @@ __global__ __launch_bounds__(256) void ll_unembed_direction_kernel(const uint16_
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int n16 = d >> 3;
-  for (int r0 = (blockIdx.x * 4 + wave) * 4; r0 < V; r0 += gridDim.x * 16) {
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    const uint4* rows[4];
+  for (int r0 = (blockIdx.x * 4 + wave) * UD_ROWS; r0 < V; r0 += gridDim.x * 4 * UD_ROWS) {
+    float acc[UD_ROWS];
+    const uint4* rows[UD_ROWS];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) rows[i] = reinterpret_cast<const uint4*>(W + (int64_t)min(r0 + i, V - 1) * d);
+    for (int i = 0; i < UD_ROWS; ++i) {
+      acc[i] = 0.f;
+      rows[i] = reinterpret_cast<const uint4*>(W + (int64_t)min(r0 + i, V - 1) * d);
+    }
     for (int c = lane; c < n16; c += 64) {
+      uint4 q[UD_ROWS];
+#pragma unroll
+      for (int i = 0; i < UD_ROWS; ++i) q[i] = rows[i][c];   // all loads of the step in flight before the first use
       const float4 v0 = *reinterpret_cast<const float4*>(sv + 8 * c);
       const float4 v1 = *reinterpret_cast<const float4*>(sv + 8 * c + 4);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint4 q = rows[i][c];
+      for (int i = 0; i < UD_ROWS; ++i) {
         float a = acc[i];
-        a = fmaf(bf16_lo(q.x), v0.x, a);
-        a = fmaf(bf16_hi(q.x), v0.y, a);
-        a = fmaf(bf16_lo(q.y), v0.z, a);
-        a = fmaf(bf16_hi(q.y), v0.w, a);
-        a = fmaf(bf16_lo(q.z), v1.x, a);
-        a = fmaf(bf16_hi(q.z), v1.y, a);
-        a = fmaf(bf16_lo(q.w), v1.z, a);
-        a = fmaf(bf16_hi(q.w), v1.w, a);
+        a = fmaf(bf16_lo(q[i].x), v0.x, a);
+        a = fmaf(bf16_hi(q[i].x), v0.y, a);
+        a = fmaf(bf16_lo(q[i].y), v0.z, a);
+        a = fmaf(bf16_hi(q[i].y), v0.w, a);
+        a = fmaf(bf16_lo(q[i].z), v1.x, a);
+        a = fmaf(bf16_hi(q[i].z), v1.y, a);
+        a = fmaf(bf16_lo(q[i].w), v1.z, a);
+        a = fmaf(bf16_hi(q[i].w), v1.w, a);
         acc[i] = a;
       }
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < UD_ROWS; ++i) {
       const float u = wave_sum(acc[i]);
       if (lane == 0 && r0 + i < V) {
 #pragma unroll
